@@ -1,0 +1,147 @@
+/*
+ * libfls - Load-as-Sparse / Compute-as-Dense SpMM for AMD MI355X (gfx950).
+ *
+ * C ABI of the hot path of Flash-LLM (arxiv 2309.10285): C = W . X with W an fp16 weight
+ * matrix [M, K] whose pruned entries are zero, kept in HBM in the Tiled-CSL compressed
+ * format, and X a skinny fp16 activation matrix [K, N] (paper Sec. 2.2: C = A x B,
+ * A = weights [M, K], B = feature map [K, N]).
+ *
+ * Conventions shared by every call
+ *   - "dev" pointers are device (HBM) addresses owned by the caller; "host" pointers are host
+ *     addresses.  The library never allocates or frees device memory.
+ *   - W dense    : fp16, row-major M x K, leading dimension K      (Alg. 3: A + x*K + y)
+ *   - X          : fp16, column-major K x N, leading dimension K   (== row-major [N][K])
+ *   - C          : fp16, column-major M x N, leading dimension M   (== row-major [N][M])
+ *   - products are exact, accumulation is fp32, C is rounded once to fp16 (nearest even)
+ *   - M must be a multiple of FLS_TILE_M, K of FLS_TILE_K; 1 <= N <= FLS_MAX_N
+ *   - device pointers must be 16-byte aligned
+ *   - kernels are enqueued on `stream` and the call returns without waiting, except
+ *     fls_compress, which waits for its own work (it is an offline step, Sec. 5)
+ *   - every function returns FLS_OK (0) or a negative error code; arguments are checked on
+ *     the host before anything is launched, so a failed call has launched nothing
+ *   - one device per process is assumed: calls act on the current HIP device
+ */
+#ifndef FLS_H_
+#define FLS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FLS_TILE_M 128u /* rows of a Tiled-CSL tile                        (Sec. 4.3.1) */
+#define FLS_TILE_K 32u  /* columns (K extent) of a Tiled-CSL tile */
+#define FLS_PAD_WORDS 4u /* a tile's run is padded to a multiple of this many words */
+#define FLS_MAX_N 256
+#define FLS_FORMAT_VERSION 1u
+#define FLS_HEADER_BYTES 64u
+
+enum {
+  FLS_OK = 0,
+  FLS_EINVAL = -1,     /* null pointer, M/K not multiples of the tile, N out of range, bad policy */
+  FLS_EALIGN = -2,     /* a device pointer is not 16-byte aligned */
+  FLS_ECAPACITY = -3,  /* output buffer too small; stats->bytes_total holds the size needed */
+  FLS_EFORMAT = -4,    /* blob header: bad magic / version / geometry, or M, K differ from the call */
+  FLS_EWORKSPACE = -5, /* no workspace registered, or it is too small for this call */
+  FLS_EHIP = -6        /* a HIP call failed (the HIP error stays readable with hipGetLastError) */
+};
+
+/* opaque stream handle: pass a hipStream_t (NULL = the default stream) */
+typedef void* fls_stream_t;
+
+/* Word order inside a tile's run (Sec. 4.3.3).  Both orders decode to the same tile. */
+enum {
+  FLS_ORDER_LOCATION = 0, /* ascending in-tile location */
+  FLS_ORDER_BANK = 1      /* ahead-of-time reordering by LDS bank (Alg. 3) */
+};
+
+typedef struct {
+  uint32_t format_version, tile_m, tile_k, order_policy;
+  uint64_t M, K, nnz, num_tiles, max_tile_words;
+  uint64_t bytes_total;    /* the whole blob: what fls_spmm streams from HBM */
+  uint64_t bytes_header;   /* 64 */
+  uint64_t bytes_offsets;  /* TileOffsets incl. look-ahead guard entries */
+  uint64_t bytes_nonzeros; /* NonZeros incl. padding words */
+} fls_stats;
+
+/*
+ * Compressed blob ("Tiled-CSL", Sec. 4.3.1; word layout Sec. 4.3.2; tile walk Alg. 3), little endian:
+ *   [0,64)   header: u32 magic "FLS1", u32 version, u32 tile_m, u32 tile_k, u32 pad_words,
+ *            u32 order_policy, u32 max_tile_words, u32 0, u64 M, u64 K, u64 nnz, u64 total_words
+ *   [64, 64 + 4*n_off)  TileOffsets: u32 word offset of each tile's run in NonZeros; tile id =
+ *            band*(K/tile_k) + ktile (row bands outer); entry num_tiles = total_words, repeated
+ *            up to n_off = round_up(num_tiles + 4, 16) entries
+ *   then     NonZeros: u32 words = (fp16 bits << 16) | location, location =
+ *            (y/8)*(tile_m*8) + x*8 + y%8 for row x, column y of the tile (the element's place in
+ *            the on-chip [K-chunk][row][8] tile); every element whose bit pattern is not 0x0000 is
+ *            stored; runs are padded with the word tile_m*tile_k (value +0, location one past the tile).
+ */
+
+/* Size in bytes of the largest blob an M x K matrix can produce (every element stored).
+ * Errors: FLS_EINVAL. */
+int fls_compress_bound(int64_t M, int64_t K, size_t* bytes_host);
+
+/*
+ * Dense masked W -> Tiled-CSL blob (the paper's offline weight reformatting step, Sec. 5, Alg. 3).
+ *   W_dev        in : fp16 row-major M x K, pruned entries exactly +0 (0x0000)
+ *   out_dev      out: blob; caller-owned, out_capacity bytes, 16-byte aligned
+ *   order_policy in : FLS_ORDER_LOCATION or FLS_ORDER_BANK
+ *   stats_host   out: may be NULL; filled on FLS_OK, and bytes_total also on FLS_ECAPACITY
+ * The result is a pure function of (W bits, M, K, order_policy).  Waits for its own kernels.
+ * Uses the start of out_dev as scratch, so out_capacity must cover header and TileOffsets even
+ * for an all-zero matrix.  Errors: FLS_EINVAL, FLS_EALIGN, FLS_ECAPACITY, FLS_EHIP.
+ */
+int fls_compress(const void* W_dev, int64_t M, int64_t K, void* out_dev, size_t out_capacity,
+                 int order_policy, fls_stats* stats_host, fls_stream_t stream);
+
+/* Validates a 64-byte header copied to the host and derives the section sizes.
+ * Errors: FLS_EINVAL (null), FLS_EFORMAT. */
+int fls_inspect(const void* header_host, fls_stats* stats_host);
+
+/*
+ * Bytes of device workspace fls_spmm / fls_dense_gemm need for this shape (split-K fp32
+ * accumulation plane and arrival counters).  Returns 0 on invalid arguments.
+ */
+size_t fls_workspace_bytes(int64_t M, int64_t K, int64_t N);
+
+/*
+ * Registers a caller-owned workspace (16-byte aligned) and clears it on `stream`.  The
+ * workspace must stay valid, and untouched by the caller, until replaced.  Kernels leave it
+ * clear when they finish, so one registration serves any number of calls; calls that share it
+ * must not overlap in time.  Errors: FLS_EINVAL, FLS_EALIGN, FLS_EHIP.
+ */
+int fls_set_workspace(void* ws_dev, size_t bytes, fls_stream_t stream);
+
+/*
+ * C = W . X with W given as a Tiled-CSL blob (the SpMM of Alg. 1): streams the blob once from
+ * HBM, rebuilds each tile densely in LDS, multiplies with MFMA, fp32 accumulation.
+ *   Wc_dev in : blob made by fls_compress (or byte-identical); its header must match M, K
+ *   X_dev  in : fp16 column-major K x N;  C_dev out: fp16 column-major M x N (fully overwritten)
+ * The first call on a given blob address reads its 64-byte header back (a blocking copy) to
+ * validate it and to pick the kernel variant; later calls on that address do not.  Call
+ * fls_forget after overwriting a blob in place with a different one.
+ * Errors: FLS_EINVAL, FLS_EALIGN, FLS_EFORMAT, FLS_EWORKSPACE, FLS_EHIP.
+ */
+int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int64_t K, int64_t N,
+             fls_stream_t stream);
+
+/* Drops what fls_spmm remembers about a blob address (NULL: about all of them). */
+void fls_forget(const void* Wc_dev);
+
+/*
+ * C = W . X with W dense (fp16 row-major M x K): the dense baseline every sparse point is
+ * paired with (the paper's own re-implemented dense GEMM, Sec. 6.2).  Same X, C, N rules and
+ * workspace as fls_spmm.  Errors: FLS_EINVAL, FLS_EALIGN, FLS_EWORKSPACE, FLS_EHIP.
+ */
+int fls_dense_gemm(const void* W_dev, const void* X_dev, void* C_dev, int64_t M, int64_t K,
+                   int64_t N, fls_stream_t stream);
+
+/* Static description of an error code. */
+const char* fls_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLS_H_ */

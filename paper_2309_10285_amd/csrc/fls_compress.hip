@@ -1,0 +1,196 @@
+// fls_compress: dense masked W -> Tiled-CSL blob on the GPU (the paper's offline weight
+// reformatting step, Sec. 5; format Sec. 4.3.1-4.3.2; tile walk of Alg. 3).
+//
+// Three kernels, all integer work on fp16 bit patterns (no value passes through a float op):
+//   count : one wave per tile counts the non-zero bit patterns -> padded run length, written
+//           in place into the TileOffsets section; nnz and the longest run go to the header
+//   scan  : one workgroup turns the run lengths into exclusive prefix sums, fills the guard
+//           entries and the rest of the header
+//   emit  : one wave per tile walks the tile in location order; per step every lane holds the 8
+//           halves of one (row, K-chunk) cell, a wave prefix sum of the per-lane counts gives each
+//           lane its slot in the run (ordered compaction)
+#include "fls_device.h"
+#include "fls_launch.h"
+
+namespace fls {
+
+constexpr uint32_t kMagic = 0x31534C46u;  // "FLS1"
+constexpr uint32_t kPad = 4;
+
+struct CompressParams {
+  const uint16_t* W;
+  unsigned char* out;
+  uint32_t M, K, KT, T, n_off, policy;
+};
+
+__device__ __forceinline__ uint32_t* offs_of(const CompressParams& p) { return (uint32_t*)(p.out + 64); }
+__device__ __forceinline__ uint32_t* words_of(const CompressParams& p) { return (uint32_t*)(p.out + 64 + 4 * (size_t)p.n_off); }
+
+__device__ __forceinline__ uint32_t nonzero_mask(const u32x4& v) {
+  uint32_t m = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    m |= ((v[i] & 0xffffu) != 0u ? 1u : 0u) << (2 * i);
+    m |= ((v[i] >> 16) != 0u ? 1u : 0u) << (2 * i + 1);
+  }
+  return m;
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+  return v;
+}
+
+// inclusive prefix sum over the 64 lanes
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, int lane) {
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t up = __shfl_up(v, d, 64);
+    if (lane >= d) v += up;
+  }
+  return v;
+}
+
+__global__ __launch_bounds__(256) void compress_count_kernel(CompressParams p) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= p.T) return;
+  const uint32_t band = t / p.KT, kt = t - band * p.KT;
+  // lane covers rows (lane >> 2) + 16*i, K chunk (lane & 3): 16 rows x 64 B per step
+  const uint16_t* src = p.W + ((size_t)band * kTileM + (lane >> 2)) * p.K + kt * kTileK + (lane & 3) * 8;
+  uint32_t cnt = 0;
+#pragma unroll
+  for (int i = 0; i < kTileM / 16; ++i) {
+    const u32x4 v = *(const u32x4*)(src + (size_t)i * 16 * p.K);
+    cnt += __popc(nonzero_mask(v));
+  }
+  cnt = wave_sum(cnt);
+  if (lane == 0) {
+    const uint32_t words = (cnt + kPad - 1) / kPad * kPad;
+    offs_of(p)[t] = words;
+    atomicAdd((unsigned long long*)(p.out + 48), (unsigned long long)cnt);  // header.nnz
+    atomicMax((uint32_t*)(p.out + 24), words);                              // header.max_tile_words
+  }
+}
+
+// single workgroup of 1024 threads
+__global__ __launch_bounds__(1024) void compress_scan_kernel(CompressParams p) {
+  __shared__ unsigned long long part[1024];
+  uint32_t* offs = offs_of(p);
+  const uint32_t tid = threadIdx.x;
+  const uint32_t per = (p.T + 1023) / 1024;
+  const uint32_t a = tid * per < p.T ? tid * per : p.T, b = (tid + 1) * per < p.T ? (tid + 1) * per : p.T;
+  unsigned long long s = 0;
+  for (uint32_t i = a; i < b; ++i) s += offs[i];
+  part[tid] = s;
+  __syncthreads();
+  // Hillis-Steele inclusive scan over the 1024 partial sums
+  for (uint32_t d = 1; d < 1024; d <<= 1) {
+    unsigned long long v = tid >= d ? part[tid - d] : 0;
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  unsigned long long run = tid ? part[tid - 1] : 0;
+  const unsigned long long total = part[1023];
+  for (uint32_t i = a; i < b; ++i) {
+    const uint32_t w = offs[i];
+    offs[i] = (uint32_t)run;
+    run += w;
+  }
+  for (uint32_t i = p.T + tid; i < p.n_off; i += 1024) offs[i] = (uint32_t)total;
+  if (tid == 0) {
+    uint32_t* h = (uint32_t*)p.out;
+    h[0] = kMagic;
+    h[1] = 1u;
+    h[2] = kTileM;
+    h[3] = kTileK;
+    h[4] = kPad;
+    h[5] = p.policy;
+    // h[6] = max_tile_words (count kernel), h[7] = 0
+    unsigned long long* q = (unsigned long long*)(p.out + 32);
+    q[0] = p.M;
+    q[1] = p.K;
+    // q[2] = nnz (count kernel)
+    q[3] = total;
+  }
+}
+
+__global__ __launch_bounds__(256) void compress_emit_kernel(CompressParams p) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= p.T) return;
+  const uint32_t band = t / p.KT, kt = t - band * p.KT;
+  const uint32_t* offs = offs_of(p);
+  uint32_t* dst = words_of(p) + offs[t];
+  const uint32_t run_words = offs[t + 1] - offs[t];
+  uint32_t pos = 0;
+  // location order: K chunk, then row, then position in the chunk
+  for (uint32_t c = 0; c < kTileK / 8; ++c) {
+    for (uint32_t half = 0; half < kTileM / 64; ++half) {
+      const uint32_t row = half * 64 + lane;
+      const u32x4 v = *(const u32x4*)(p.W + ((size_t)band * kTileM + row) * p.K + kt * kTileK + c * 8);
+      const uint32_t mask = nonzero_mask(v);
+      const uint32_t cnt = __popc(mask);
+      const uint32_t incl = wave_inclusive_scan(cnt, lane);
+      uint32_t slot = pos + incl - cnt;
+      const uint32_t loc0 = c * (kTileM * 8) + row * 8;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (mask >> e & 1u) {
+          const uint32_t bits = (e & 1) ? (v[e >> 1] >> 16) : (v[e >> 1] & 0xffffu);
+          dst[slot++] = (bits << 16) | (loc0 + e);
+        }
+      }
+      pos += __shfl(incl, 63, 64);
+    }
+  }
+  // padding words: value +0, location one past the tile
+  if (pos + lane < run_words) dst[pos + lane] = (uint32_t)kTileElems;
+}
+
+__global__ void fill_zero_kernel(u32x4* p, size_t n16) {
+  const u32x4 z = {0u, 0u, 0u, 0u};
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) p[i] = z;
+}
+
+hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream) {
+  const size_t n16 = bytes / 16;
+  if (n16 == 0) return hipSuccess;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (u32x4*)ptr, n16);
+  return hipGetLastError();
+}
+
+static CompressParams make_params(const CompressLaunch& a) {
+  CompressParams p;
+  p.W = a.W;
+  p.out = a.out;
+  p.M = a.M;
+  p.K = a.K;
+  p.KT = a.K / kTileK;
+  p.T = (a.M / kTileM) * p.KT;
+  p.n_off = (p.T + 4 + 15) / 16 * 16;
+  p.policy = a.policy;
+  return p;
+}
+
+hipError_t launch_compress_index(const CompressLaunch& a, hipStream_t stream) {
+  const CompressParams p = make_params(a);
+  hipError_t e = launch_fill_zero(a.out, 64, stream);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(compress_count_kernel, dim3((p.T + 3) / 4), dim3(256), 0, stream, p);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(compress_scan_kernel, dim3(1), dim3(1024), 0, stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_compress_emit(const CompressLaunch& a, hipStream_t stream) {
+  const CompressParams p = make_params(a);
+  hipLaunchKernelGGL(compress_emit_kernel, dim3((p.T + 3) / 4), dim3(256), 0, stream, p);
+  return hipGetLastError();
+}
+
+}  // namespace fls

@@ -1,0 +1,45 @@
+// Host-side launch descriptors: the C ABI layer fills these, each kernel file implements its launcher.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fls {
+
+struct SpmmLaunch {
+  const uint32_t* offs;   // TileOffsets section of the blob
+  const uint32_t* words;  // NonZeros section of the blob
+  const _Float16* X;
+  _Float16* C;
+  float* plane;
+  uint32_t* cnt;
+  uint32_t M, K, N;
+  uint32_t max_tile_words;
+  int num_cus;
+};
+
+struct DenseLaunch {
+  const _Float16* W;
+  const _Float16* X;
+  _Float16* C;
+  float* plane;
+  uint32_t* cnt;
+  uint32_t M, K, N;
+  int num_cus;
+};
+
+struct CompressLaunch {
+  const uint16_t* W;
+  unsigned char* out;  // blob
+  uint32_t M, K;
+  uint32_t policy;
+};
+
+hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream);
+hipError_t launch_dense(const DenseLaunch& a, hipStream_t stream);
+// phase 1: per-tile counts, prefix sums, header (everything but the words)
+hipError_t launch_compress_index(const CompressLaunch& a, hipStream_t stream);
+// phase 2: the words
+hipError_t launch_compress_emit(const CompressLaunch& a, hipStream_t stream);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
+
+}  // namespace fls

@@ -1,0 +1,240 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Bars: compressed buffers bit-exact; C within max|C - C_ref| / max|C_ref| <= 2e-3 after fp16 output
+rounding (products exact, fp32 accumulation, one fp16 rounding; the bound is the task's stated tolerance).
+"""
+import numpy as np
+import pytest
+
+import fls_workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def fls():
+    import torch
+
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2309_10285_amd as f
+
+    f.lib()  # raises if the HIP library was not built: there is no fallback
+    return f
+
+
+def _dev_w(bits):
+    import torch
+
+    return torch.from_numpy(bits.view(np.float16)).cuda()
+
+
+def _rel_err(C_gpu, C_ref):
+    scale = max(float(np.abs(C_ref).max()), 1e-30)
+    return float(np.abs(C_gpu.astype(np.float64) - C_ref).max()) / scale
+
+
+def _run_spmm(fls, Wbits, Xbits, N):
+    import torch
+
+    M, K = Wbits.shape
+    blob, st = fls.fls_compress(_dev_w(Wbits))
+    X = torch.from_numpy(Xbits.view(np.float16)).cuda()
+    C = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+    fls.ensure_workspace(M, K, N)
+    fls.fls_spmm(blob, X, C, M, K, N)
+    torch.cuda.synchronize()
+    return blob, st, C.cpu().numpy()
+
+
+def _run_dense(fls, Wbits, Xbits, N):
+    import torch
+
+    M, K = Wbits.shape
+    X = torch.from_numpy(Xbits.view(np.float16)).cuda()
+    C = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+    fls.ensure_workspace(M, K, N)
+    fls.fls_dense_gemm(_dev_w(Wbits), X, C, M, K, N)
+    torch.cuda.synchronize()
+    return C.cpu().numpy()
+
+
+def _cases():
+    g = np.random.Generator(np.random.Philox(2024))
+    out = []
+    # (name, M, K, beta, mask)
+    for name, M, K, beta, mask in [
+        ("one-tile", 128, 32, 0.8, "uniform"),
+        ("one-band", 128, 1024, 0.8, "uniform"),
+        ("ragged-7x9-tiles", 896, 288, 0.7, "uniform"),
+        ("C1", 1024, 1024, 0.8, "uniform"),
+        ("magnitude-90", 1536, 2048, 0.9, "magnitude"),
+        ("half-dense", 640, 512, 0.5, "uniform"),
+        ("dense-0pct", 384, 256, 0.0, "uniform"),
+        ("row-skewed", 2048, 1024, 0.8, "row_skewed"),
+        ("many-bands-short-k", 8192, 64, 0.8, "uniform"),
+    ]:
+        W32 = wl.gen_weights_f32(M, K, int(g.integers(1 << 30)))
+        if mask == "uniform":
+            W = wl.prune_uniform(W32, beta, 7) if beta > 0 else wl.dense_bits(W32)
+        elif mask == "magnitude":
+            W = wl.prune_magnitude(W32, beta)
+        else:
+            W = wl.prune_row_skewed(W32, beta, 7)
+        out.append((name, W))
+    return out
+
+
+CASES = _cases()
+
+
+@pytest.mark.parametrize("name,W", CASES, ids=[c[0] for c in CASES])
+def test_compress_bit_exact(fls, oracle_mod, name, W):
+    blob, st = fls.fls_compress(_dev_w(W))
+    ref = oracle_mod.ref_compress(W)
+    got = blob.cpu().numpy()
+    assert got.size == ref.size == st["bytes_total"]
+    assert np.array_equal(got, ref)
+    info = oracle_mod.ref_inspect(ref)
+    assert st["nnz"] == info["nnz"] == int(np.count_nonzero(W))
+    assert st["max_tile_words"] == info["max_tile_words"] and st["num_tiles"] == info["num_tiles"]
+    assert fls.fls_inspect(got[:64].tobytes())["bytes_total"] == ref.size
+
+
+def test_compress_special_values_and_edge_tiles(fls, oracle_mod):
+    g = np.random.Generator(np.random.Philox(8))
+    M, K = 384, 128
+    bits = g.integers(0, 65536, size=(M, K), dtype=np.uint32).astype(np.uint16)  # NaN, Inf, -0, subnormals
+    W = np.where(g.random((M, K)) < 0.3, bits, np.uint16(0))
+    W[:128, :32] = 0                      # an empty tile
+    W[128:256, 32:64] = bits[128:256, 32:64] | 1   # a full tile
+    W[256, 0] = 0x8000                    # -0.0 at the first location
+    W[383, 127] = 0x7E01                  # NaN payload at the last location
+    blob, st = fls.fls_compress(_dev_w(W))
+    ref = oracle_mod.ref_compress(W)
+    assert np.array_equal(blob.cpu().numpy(), ref)
+    assert np.array_equal(oracle_mod.ref_decompress(blob.cpu().numpy(), M, K), W)
+    # all-zero matrix
+    Z = np.zeros((256, 64), dtype=np.uint16)
+    blob, st = fls.fls_compress(_dev_w(Z))
+    assert st["nnz"] == 0 and np.array_equal(blob.cpu().numpy(), oracle_mod.ref_compress(Z))
+
+
+@pytest.mark.parametrize("name,W", CASES, ids=[c[0] for c in CASES])
+@pytest.mark.parametrize("N", [1, 8, 16, 17, 32, 64])
+def test_spmm_matches_oracle(fls, oracle_mod, name, W, N):
+    M, K = W.shape
+    X = wl.gen_x(N, K, 99 + N)
+    _, _, C = _run_spmm(fls, W, X, N)
+    ref = oracle_mod.ref_spmm_f64(W, X)
+    assert np.isfinite(C).all()
+    assert _rel_err(C, ref) <= TOL
+
+
+@pytest.mark.parametrize("N", [100, 128, 256])
+def test_spmm_wide_n(fls, oracle_mod, N):
+    W = CASES[3][1]
+    M, K = W.shape
+    X = wl.gen_x(N, K, 5)
+    _, _, C = _run_spmm(fls, W, X, N)
+    assert _rel_err(C, oracle_mod.ref_spmm_f64(W, X)) <= TOL
+
+
+def test_spmm_small_integers_exact(fls, oracle_mod):
+    # every partial sum is an integer below 2^24: fp32 accumulation in any order is exact, and so is fp16 output
+    g = np.random.Generator(np.random.Philox(4))
+    M, K, N = 512, 640, 24
+    Wi = g.integers(-3, 4, size=(M, K))
+    Wi[g.random((M, K)) < 0.8] = 0
+    Xi = g.integers(-2, 3, size=(N, K))
+    W = Wi.astype(np.float16).view(np.uint16)
+    X = Xi.astype(np.float16).view(np.uint16)
+    _, _, C = _run_spmm(fls, W, X, N)
+    ref = oracle_mod.ref_spmm_f64(W, X)
+    assert np.abs(ref).max() < 2048
+    assert np.array_equal(C.astype(np.float64), ref)
+    assert np.array_equal(_run_dense(fls, W, X, N).astype(np.float64), ref)
+
+
+def test_spmm_identity_x_returns_columns(fls):
+    W = CASES[3][1][:, :64].copy()
+    M, K = W.shape
+    X = np.zeros((64, 64), dtype=np.uint16)
+    X[np.arange(64), np.arange(64)] = 0x3C00
+    _, _, C = _run_spmm(fls, W, X, 64)
+    assert np.array_equal(C.view(np.uint16), W.T)  # bit exact, incl. zeros
+
+
+def test_spmm_zero_matrix_and_repeat_calls(fls, oracle_mod):
+    import torch
+
+    Z = np.zeros((256, 128), dtype=np.uint16)
+    X = wl.gen_x(16, 128, 1)
+    _, _, C = _run_spmm(fls, Z, X, 16)
+    assert np.count_nonzero(C) == 0
+    # the workspace must come back clean: repeated calls give the same answer
+    W = CASES[3][1]
+    M, K = W.shape
+    X = wl.gen_x(16, K, 2)
+    ref = oracle_mod.ref_spmm_f64(W, X)
+    blob, _ = fls.fls_compress(_dev_w(W))
+    Xd = torch.from_numpy(X.view(np.float16)).cuda()
+    fls.ensure_workspace(M, K, 16)
+    for _ in range(5):
+        C = torch.zeros((16, M), dtype=torch.float16, device="cuda")
+        fls.fls_spmm(blob, Xd, C, M, K, 16)
+        torch.cuda.synchronize()
+        assert _rel_err(C.cpu().numpy(), ref) <= TOL
+
+
+def test_spmm_order_invariance(fls, oracle_mod):
+    """Sec. 4.3.3: reordering a tile's words changes global-memory order only; the kernel result stays."""
+    import torch
+
+    W = CASES[3][1]
+    M, K = W.shape
+    N = 16
+    X = wl.gen_x(N, K, 3)
+    ref = oracle_mod.ref_spmm_f64(W, X)
+    blob = oracle_mod.ref_compress(W, policy=1)      # an oracle-made blob in the other word order
+    blob[20:24] = 0                                  # keep the header's policy field within what the library takes
+    bd = torch.from_numpy(blob).cuda()
+    Xd = torch.from_numpy(X.view(np.float16)).cuda()
+    C = torch.zeros((N, M), dtype=torch.float16, device="cuda")
+    fls.ensure_workspace(M, K, N)
+    fls.fls_spmm(bd, Xd, C, M, K, N)
+    torch.cuda.synchronize()
+    assert _rel_err(C.cpu().numpy(), ref) <= TOL
+
+
+@pytest.mark.parametrize("name,W", CASES[:6], ids=[c[0] for c in CASES[:6]])
+@pytest.mark.parametrize("N", [8, 16, 40, 64, 256])
+def test_dense_gemm_matches_oracle(fls, oracle_mod, name, W, N):
+    M, K = W.shape
+    X = wl.gen_x(N, K, 17 + N)
+    C = _run_dense(fls, W, X, N)
+    assert _rel_err(C, oracle_mod.ref_spmm_f64(W, X)) <= TOL
+
+
+def test_error_codes_on_device(fls):
+    import torch
+
+    W = _dev_w(CASES[0][1])
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    with pytest.raises(fls.FlsError) as e:
+        fls.fls_compress(W, out=small)
+    assert e.value.code == fls.ECAPACITY
+    blob, _ = fls.fls_compress(W)
+    X = torch.zeros((8, 32), dtype=torch.float16, device="cuda")
+    C = torch.zeros((8, 128), dtype=torch.float16, device="cuda")
+    fls.ensure_workspace(256, 32, 8)
+    bad = blob.clone()
+    bad[0] = 0
+    rc = fls.lib().fls_spmm(bad.data_ptr(), X.data_ptr(), C.data_ptr(), 128, 32, 8, None)
+    assert rc == fls.EFORMAT
+    rc = fls.lib().fls_spmm(blob.data_ptr(), X.data_ptr(), C.data_ptr(), 256, 32, 8, None)
+    assert rc == fls.EFORMAT  # header says 128 rows
+    rc = fls.lib().fls_spmm(blob.data_ptr() + 2, X.data_ptr(), C.data_ptr(), 128, 32, 8, None)
+    assert rc == fls.EALIGN
