@@ -101,8 +101,8 @@ int fls_compress(const void* W_dev, int64_t M, int64_t K, void* out_dev, size_t 
 int fls_inspect(const void* header_host, fls_stats* stats_host);
 
 /*
- * Bytes of device workspace fls_spmm / fls_dense_gemm need for this shape (split-K fp32
- * accumulation plane and arrival counters).  Returns 0 on invalid arguments.
+ * Bytes of device workspace fls_spmm / fls_dense_gemm need for this shape (split-K partial
+ * sums and arrival counters; it grows with N only).  Returns 0 on invalid arguments.
  */
 size_t fls_workspace_bytes(int64_t M, int64_t K, int64_t N);
 

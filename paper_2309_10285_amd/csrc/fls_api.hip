@@ -94,12 +94,13 @@ int check_mm_args(const void* W, const void* X, void* C, int64_t M, int64_t K, i
   return FLS_OK;
 }
 
-// plane [M][round_up(N,16)] fp32 followed by one u32 counter per band
-void workspace_layout(int64_t M, int64_t N, size_t* plane_bytes, size_t* total) {
-  const size_t plane = (size_t)M * round_up((uint64_t)N, 16) * sizeof(float);
-  const size_t cnt = round_up((uint64_t)(M / FLS_TILE_M) * sizeof(uint32_t), 16);
-  *plane_bytes = plane;
-  *total = plane + cnt;
+// Workspace: a fixed 4 MiB area of u32 arrival counters, one per row band (M * K < 2^32 and
+// K >= 32 bound the bands by 2^20), then the split-K partial slots (fp32).  The counter area has
+// the same place for every shape, so partial sums of one call can never be read as counters by
+// the next.
+constexpr size_t kCounterAreaBytes = (size_t)4 << 20;
+void workspace_layout(int64_t N, size_t* total) {
+  *total = kCounterAreaBytes + fls::parts_floats((uint32_t)N) * sizeof(float);
 }
 
 }  // namespace
@@ -166,8 +167,8 @@ int fls_compress(const void* W_dev, int64_t M, int64_t K, void* out_dev, size_t 
 
 size_t fls_workspace_bytes(int64_t M, int64_t K, int64_t N) {
   if (!shape_ok(M, K) || N < 1 || N > FLS_MAX_N) return 0;
-  size_t plane, total;
-  workspace_layout(M, N, &plane, &total);
+  size_t total;
+  workspace_layout(N, &total);
   return total;
 }
 
@@ -191,8 +192,8 @@ int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int6
              fls_stream_t stream) {
   int rc = check_mm_args(Wc_dev, X_dev, C_dev, M, K, N);
   if (rc != FLS_OK) return rc;
-  size_t plane_bytes, need;
-  workspace_layout(M, N, &plane_bytes, &need);
+  size_t need;
+  workspace_layout(N, &need);
   void* ws;
   BlobInfo info;
   bool known;
@@ -224,8 +225,8 @@ int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int6
   a.words = a.offs + info.n_off;
   a.X = (const _Float16*)X_dev;
   a.C = (_Float16*)C_dev;
-  a.plane = (float*)ws;
-  a.cnt = (uint32_t*)((unsigned char*)ws + plane_bytes);
+  a.cnt = (uint32_t*)ws;
+  a.parts = (float*)((unsigned char*)ws + kCounterAreaBytes);
   a.M = (uint32_t)M;
   a.K = (uint32_t)K;
   a.N = (uint32_t)N;
@@ -238,8 +239,8 @@ int fls_dense_gemm(const void* W_dev, const void* X_dev, void* C_dev, int64_t M,
                    fls_stream_t stream) {
   int rc = check_mm_args(W_dev, X_dev, C_dev, M, K, N);
   if (rc != FLS_OK) return rc;
-  size_t plane_bytes, need;
-  workspace_layout(M, N, &plane_bytes, &need);
+  size_t need;
+  workspace_layout(N, &need);
   void* ws;
   {
     std::lock_guard<std::mutex> lk(g_mu);
@@ -252,8 +253,8 @@ int fls_dense_gemm(const void* W_dev, const void* X_dev, void* C_dev, int64_t M,
   a.W = (const _Float16*)W_dev;
   a.X = (const _Float16*)X_dev;
   a.C = (_Float16*)C_dev;
-  a.plane = (float*)ws;
-  a.cnt = (uint32_t*)((unsigned char*)ws + plane_bytes);
+  a.cnt = (uint32_t*)ws;
+  a.parts = (float*)((unsigned char*)ws + kCounterAreaBytes);
   a.M = (uint32_t)M;
   a.K = (uint32_t)K;
   a.N = (uint32_t)N;

@@ -13,7 +13,6 @@ struct DenseParams {
   const _Float16* W;
   const _Float16* X;
   uint32_t K;
-  uint32_t T;
   OutParams out;
 };
 
@@ -22,7 +21,13 @@ __global__ __launch_bounds__(WAVES * 64) void dense_kernel(DenseParams p) {
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t g = blockIdx.x * WAVES + wave, G = gridDim.x * WAVES;
-  const uint32_t t0 = (uint32_t)((uint64_t)g * p.T / G), t1 = (uint32_t)((uint64_t)(g + 1) * p.T / G);
+  const uint32_t T = p.out.T;
+  const uint32_t t0 = (uint32_t)((uint64_t)g * T / G), t1 = (uint32_t)((uint64_t)(g + 1) * T / G);
+  const uint32_t share0 = share_begin(blockIdx.x, T, gridDim.x), share1 = share_begin(blockIdx.x + 1, T, gridDim.x);
+  extern __shared__ __align__(16) unsigned char lds[];
+  WgReduceLds<NB>* red = (WgReduceLds<NB>*)lds;
+  wg_reduce_init<NB>(red, threadIdx.x, WAVES * 64);
+  __syncthreads();  // the only barrier
   if (t0 >= t1) return;
   const uint32_t KT = p.out.KT;
 
@@ -32,6 +37,8 @@ __global__ __launch_bounds__(WAVES * 64) void dense_kernel(DenseParams p) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[rb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
 
+  XFrags xf;
+  xf.init(p.X, p.K, p.out.N, p.out.n0, lane);
   // lane l of row block rb reads row rb*16 + (l & 15), k chunk (l >> 4)
   const size_t lane_off = (size_t)(lane & 15) * p.K + (lane >> 4) * 8;
 
@@ -42,7 +49,7 @@ __global__ __launch_bounds__(WAVES * 64) void dense_kernel(DenseParams p) {
 #pragma unroll
     for (int rb = 0; rb < kRowBlocks; ++rb)
       a[rb] = __builtin_nontemporal_load((const half8*)(src + (size_t)rb * 16 * p.K));
-    load_x_frags<NB>(x, p.X, p.K, p.out.N, p.out.n0, kt, lane);
+    xf.template load<NB>(x, kt);
   };
 
   uint32_t piece_tiles = 0;
@@ -54,7 +61,18 @@ __global__ __launch_bounds__(WAVES * 64) void dense_kernel(DenseParams p) {
       for (int nb = 0; nb < NB; ++nb) acc[rb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[rb], x[nb], acc[rb][nb], 0, 0, 0);
     ++piece_tiles;
     if (kt + 1 == KT || t + 1 == t1) {
-      flush_band<NB>(p.out, acc, band, piece_tiles, lane);
+      if (piece_tiles == KT) {
+        store_band<NB>(p.out, acc, band, lane);
+        wg_reduce_skip<NB>(red, band - share0 / KT, lane);
+      } else {
+        const uint32_t band_lo = band * KT;
+        const uint32_t lo = share0 > band_lo ? share0 : band_lo;
+        const uint32_t hi = share1 < band_lo + KT ? share1 : band_lo + KT;
+        const uint32_t seq = band - share0 / KT;
+        if (wg_reduce_add<NB>(red, acc, seq, piece_tiles, hi - lo, lane))
+          finish_band<NB>(red, p.out.C, p.out.parts, p.out.cnt, p.out.M, p.out.N, p.out.n0, KT, p.out.T, seq, band, lo, hi,
+                          share0, blockIdx.x, gridDim.x, false);
+      }
       piece_tiles = 0;
 #pragma unroll
       for (int rb = 0; rb < kRowBlocks; ++rb)
@@ -77,7 +95,14 @@ __global__ __launch_bounds__(WAVES * 64) void dense_kernel(DenseParams p) {
 
 template <int NB, int WAVES>
 static hipError_t launch_dense_variant(const DenseParams& p, int grid, hipStream_t stream) {
-  hipLaunchKernelGGL((dense_kernel<NB, WAVES>), dim3(grid), dim3(WAVES * 64), 0, stream, p);
+  static bool attr_done = false;
+  const int lds_bytes = (int)sizeof(WgReduceLds<NB>);
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)dense_kernel<NB, WAVES>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL((dense_kernel<NB, WAVES>), dim3(grid), dim3(WAVES * 64), lds_bytes, stream, p);
   return hipGetLastError();
 }
 
@@ -86,21 +111,21 @@ hipError_t launch_dense(const DenseLaunch& a, hipStream_t stream) {
   p.W = a.W;
   p.X = a.X;
   p.K = a.K;
-  p.T = (a.M / kTileM) * (a.K / kTileK);
+  p.out.T = (a.M / kTileM) * (a.K / kTileK);
   p.out.C = a.C;
-  p.out.plane = a.plane;
+  p.out.parts = a.parts;
   p.out.cnt = a.cnt;
   p.out.M = a.M;
   p.out.N = a.N;
-  p.out.n_pad = (a.N + 15) / 16 * 16;
   p.out.KT = a.K / kTileK;
+  const int grid = a.num_cus < kMaxGrid ? a.num_cus : kMaxGrid;
   for (uint32_t n0 = 0; n0 < a.N; n0 += 64) {
     p.out.n0 = n0;
     const uint32_t ncols = a.N - n0 < 64 ? a.N - n0 : 64;
     hipError_t e;
-    if (ncols <= 16) e = launch_dense_variant<1, 8>(p, a.num_cus, stream);
-    else if (ncols <= 32) e = launch_dense_variant<2, 8>(p, a.num_cus, stream);
-    else e = launch_dense_variant<4, 8>(p, a.num_cus, stream);
+    if (ncols <= 16) e = launch_dense_variant<1, 8>(p, grid, stream);
+    else if (ncols <= 32) e = launch_dense_variant<2, 8>(p, grid, stream);
+    else e = launch_dense_variant<4, 8>(p, grid, stream);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;

@@ -10,7 +10,7 @@ struct SpmmLaunch {
   const uint32_t* words;  // NonZeros section of the blob
   const _Float16* X;
   _Float16* C;
-  float* plane;
+  float* parts;
   uint32_t* cnt;
   uint32_t M, K, N;
   uint32_t max_tile_words;
@@ -21,7 +21,7 @@ struct DenseLaunch {
   const _Float16* W;
   const _Float16* X;
   _Float16* C;
-  float* plane;
+  float* parts;
   uint32_t* cnt;
   uint32_t M, K, N;
   int num_cus;
@@ -33,6 +33,13 @@ struct CompressLaunch {
   uint32_t M, K;
   uint32_t policy;
 };
+
+// Columns are processed in groups of up to 64; a group of c columns runs as 1, 2 or 4 MFMA column
+// blocks of 16.
+inline uint32_t group_blocks(uint32_t ncols) { return ncols <= 16 ? 1u : (ncols <= 32 ? 2u : 4u); }
+constexpr uint32_t kMaxWorkgroups = 512;    // must equal fls::kMaxGrid of the device code
+// fp32 values of the split-K partial slots: [workgroup][2][column blocks][128 x 16]
+inline size_t parts_floats(uint32_t N) { return (size_t)kMaxWorkgroups * 2 * group_blocks(N < 64 ? N : 64) * 2048; }
 
 hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream);
 hipError_t launch_dense(const DenseLaunch& a, hipStream_t stream);

@@ -75,6 +75,10 @@ def _cases():
         ("dense-0pct", 384, 256, 0.0, "uniform"),
         ("row-skewed", 2048, 1024, 0.8, "row_skewed"),
         ("many-bands-short-k", 8192, 64, 0.8, "uniform"),
+        # shares of a workgroup that span many bands (slot turns, whole bands inside one wave)
+        ("long-share-kt1", 128 * 2304, 32, 0.8, "uniform"),
+        ("long-share-kt2", 128 * 1500, 64, 0.8, "uniform"),
+        ("long-share-kt3", 128 * 1111, 96, 0.7, "uniform"),
     ]:
         W32 = wl.gen_weights_f32(M, K, int(g.integers(1 << 30)))
         if mask == "uniform":
@@ -209,7 +213,7 @@ def test_spmm_order_invariance(fls, oracle_mod):
     assert _rel_err(C.cpu().numpy(), ref) <= TOL
 
 
-@pytest.mark.parametrize("name,W", CASES[:6], ids=[c[0] for c in CASES[:6]])
+@pytest.mark.parametrize("name,W", CASES[:6] + CASES[9:], ids=[c[0] for c in CASES[:6] + CASES[9:]])
 @pytest.mark.parametrize("N", [8, 16, 40, 64, 256])
 def test_dense_gemm_matches_oracle(fls, oracle_mod, name, W, N):
     M, K = W.shape
