@@ -6,6 +6,19 @@
 
 namespace fls {
 
+// Debug builds only (-DFLS_TRACE): 100 MHz timestamps of the hand-over steps, kept in the unused
+// tail of the counter area: cnt[65536 + 16 * workgroup + k].
+#ifdef FLS_TRACE
+#define FLS_STAMP(cnt, wg, k)                                                             \
+  do {                                                                                    \
+    if ((threadIdx.x & 63) == 0) (cnt)[65536 + 16 * (wg) + (k)] = (uint32_t)wall_clock64(); \
+  } while (0)
+#else
+#define FLS_STAMP(cnt, wg, k) \
+  do {                        \
+  } while (0)
+#endif
+
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float float4v __attribute__((ext_vector_type(4)));
@@ -21,7 +34,7 @@ constexpr int kAccPerBlock = kTileM * 16;   // fp32 values of one 128 x 16 colum
 constexpr int kMaxGrid = 512;               // workgroups a launch may use (sizes the workspace)
 constexpr int kBufferFlags = 0x00020000;    // raw buffer, 32-bit data format (gfx9 descriptor word 3)
 constexpr int kAuxNonTemporal = 2;          // nt: streamed once, do not keep in the caches
-constexpr int kAuxCoherent = 1 | 16;        // sc0 sc1: through to memory / past the caches
+constexpr int kAuxCoherent = 16;            // sc1: device scope - through to memory / past the per-XCD L2
 
 // What both kernels need to hand results over.
 //
@@ -170,11 +183,12 @@ __device__ __forceinline__ void band_handover(const OutParams& o, float4v (&acc)
   // cut-off band can be partial, so each slot is used at most once per call)
   const uint32_t my_slot = share0 < band_lo ? 1u : 0u;
   // Partial sums cross between the L2 caches of different XCDs.  They are written through to
-  // memory and read past the caches access by access (sc0 sc1 on the instruction), so that no
+  // memory and read past the caches access by access (sc1 on the instruction), so that no
   // cache-wide write-back or invalidate - what a device-scope fence costs - is needed: waiting
   // for the stores to be acknowledged orders them before the counter.  A slot is kept as
   // [column block][row block][lane] float4, 1 KB per instruction.
   constexpr int kSlotBytes = NB * kAccPerBlock * 4;
+  FLS_STAMP(o.cnt, wg, 2 + 6 * my_slot);
   {
     const __amdgpu_buffer_rsrc_t mine = __builtin_amdgcn_make_buffer_rsrc(
         (void*)(o.parts + ((size_t)wg * 2 + my_slot) * (NB * kAccPerBlock)), 0, kSlotBytes, kBufferFlags);
@@ -186,38 +200,57 @@ __device__ __forceinline__ void band_handover(const OutParams& o, float4v (&acc)
                                                ((nb * kRowBlocks + rb) * 64 + lane) * 16, 0, kAuxCoherent);
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // s_waitcnt vmcnt(0): the stores are done
+  FLS_STAMP(o.cnt, wg, 3 + 6 * my_slot);
   uint32_t old = 0;
   if (lane == 0) old = __hip_atomic_fetch_add(o.cnt + band, hi - lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   old = __builtin_amdgcn_readfirstlane(old);
+  FLS_STAMP(o.cnt, wg, 4 + 6 * my_slot);
   if (old + (hi - lo) != o.KT) return;
-  // last arrival: every share of this band is stored; add them in workgroup order
+  // last arrival: every share of this band is stored; add them in workgroup order.  The loads
+  // of up to kBatch shares are all issued before the first is used: each is a trip to memory,
+  // and this code runs when the kernel is about to end, with nothing left to hide it behind.
+  constexpr int kBatch = NB == 1 ? 4 : (NB == 2 ? 2 : 1);
   uint32_t q = (uint32_t)((uint64_t)band_lo * P / o.T);
   while (q > 0 && share_begin(q, o.T, P) > band_lo) --q;
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
     for (int rb = 0; rb < kRowBlocks; ++rb) acc[rb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
-  for (; q < P && share_begin(q, o.T, P) < band_hi; ++q) {
-    const uint32_t qb = share_begin(q, o.T, P), qe = share_begin(q + 1, o.T, P);
-    if (qe <= band_lo || qe == qb) continue;  // ends before the band, or empty
-    const uint32_t slot = qb < band_lo ? 1u : 0u;
-    const __amdgpu_buffer_rsrc_t src = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)(o.parts + ((size_t)q * 2 + slot) * (NB * kAccPerBlock)), 0, kSlotBytes, kBufferFlags);
+  while (q < P && share_begin(q, o.T, P) < band_hi) {
+    u32x4 v[kBatch][NB][kRowBlocks];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-#pragma unroll
-      for (int h = 0; h < kRowBlocks; h += 4) {  // four 1 KB loads in flight at a time
-        u32x4 v[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          v[j] = __builtin_amdgcn_raw_buffer_load_b128(src, ((nb * kRowBlocks + h + j) * 64 + lane) * 16, 0, kAuxCoherent);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[h + j][nb] += __builtin_bit_cast(float4v, v[j]);
+    for (int j = 0; j < kBatch; ++j) {
+      // next share that overlaps the band; past the last one the descriptor is empty and reads 0
+      uint32_t qb = 0, qe = 0;
+      bool found = false;
+      while (!found && q < P && share_begin(q, o.T, P) < band_hi) {
+        qb = share_begin(q, o.T, P);
+        qe = share_begin(q + 1, o.T, P);
+        found = qe > band_lo && qe != qb;
+        if (!found) ++q;
       }
+      const uint32_t slot = qb < band_lo ? 1u : 0u;
+      const __amdgpu_buffer_rsrc_t src = __builtin_amdgcn_make_buffer_rsrc(
+          (void*)(o.parts + ((size_t)(found ? q : 0u) * 2 + slot) * (NB * kAccPerBlock)), 0, found ? kSlotBytes : 0,
+          kBufferFlags);
+      if (found) ++q;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int rb = 0; rb < kRowBlocks; ++rb)
+          v[j][nb][rb] = __builtin_amdgcn_raw_buffer_load_b128(src, ((nb * kRowBlocks + rb) * 64 + lane) * 16, 0, kAuxCoherent);
     }
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int rb = 0; rb < kRowBlocks; ++rb) acc[rb][nb] += __builtin_bit_cast(float4v, v[j][nb][rb]);
   }
+  FLS_STAMP(o.cnt, wg, 5 + 6 * my_slot);
   store_band<NB>(o, acc, band, lane);
   if (lane == 0) __hip_atomic_store(o.cnt + band, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  FLS_STAMP(o.cnt, wg, 6 + 6 * my_slot);
 }
 
 // Everything the picked wave does after its own contribution, kept out of line: it runs at most

@@ -4,7 +4,7 @@
 // One persistent workgroup per CU; every wave owns a contiguous run of Tiled-CSL tiles and a
 // private 8 KB LDS tile, so the stages of Alg. 1 run per wave with no workgroup barrier:
 //   gmem2reg : the tile's words stream from HBM into VGPRs with 16 B non-temporal loads,
-//              two tiles ahead of their use (register double buffer)
+//              a few tiles ahead of their use (register ring)
 //   extract  : each word's fp16 value is stored at its location in the zero-filled LDS tile
 //              (Alg. 2); the location field already is the position in the MFMA operand layout
 //   smem2tc  : A fragments are 16 B LDS reads, B fragments (X) come straight from L2 as 16 B
@@ -35,64 +35,42 @@ struct SpmmParams {
   OutParams out;
 };
 
-// A run of at most R*256 words of one tile.
-struct Chunk {
-  uint32_t begin, n;  // word range [begin, begin + n) in NonZeros
-  uint32_t t, kt, band;  // tile id, its K tile and row band
-  bool last;   // completes its tile
-  bool valid;
-};
+// TileOffsets of 64 consecutive tiles, one per lane of a VGPR, picked with v_readlane: stepping
+// to the next tile then costs no memory access (a load per tile, scalar or vector, would put its
+// latency on the critical path of every tile).
+struct OffsetWindow {
+  const uint32_t* offs;
+  uint32_t T;       // index of the last entry that differs from its successor (offs[T] = total words)
+  uint32_t base;    // tile whose offset lane 0 holds
+  uint32_t window;  // this lane's offset
+  int lane;
 
-// TileOffsets are read through the scalar unit: the index is wave-uniform and nothing in the kernel
-// writes the blob, so the constant address space is safe and keeps these loads off the vector
-// memory counter that paces the word stream.
-typedef const __attribute__((address_space(4))) uint32_t* const_u32_ptr;
-
-template <int R>
-struct ChunkWalk {
-  const_u32_ptr offs;
-  uint32_t t, t_end, KT;
-  uint32_t pos, end, end_next;
-  uint32_t kt, band;
-
-  __device__ __forceinline__ void init(const uint32_t* offs_, uint32_t t0, uint32_t t1, uint32_t KT_) {
-    offs = (const_u32_ptr)offs_;
-    t = t0;
-    t_end = t1;
-    KT = KT_;
-    pos = offs[t0];
-    end = offs[t0 + 1];
-    end_next = offs[t0 + 2];  // guard entries keep this in bounds
-    band = t0 / KT;
-    kt = t0 - band * KT;
+  __device__ __forceinline__ void load(uint32_t t) {
+    base = t;
+    const uint32_t idx = t + (uint32_t)lane;
+    window = offs[idx < T ? idx : T];
+    // Wait for the value here, inside the (rare) reload path: if its arrival were first needed
+    // after the paths join, every tile would pay a full "wait for all loads".
+    asm volatile("" : "+v"(window));
   }
-  __device__ __forceinline__ Chunk next() {
-    Chunk c;
-    c.valid = t < t_end;
-    c.begin = pos;
-    uint32_t n = end - pos;
-    if (n > R * 256u) n = R * 256u;
-    c.n = c.valid ? n : 0u;
-    c.t = t;
-    c.kt = kt;
-    c.band = band;
-    c.last = (pos + n == end);
-    if (c.valid) {
-      pos += n;
-      if (c.last) {
-        ++t;
-        pos = end;
-        end = end_next;
-        end_next = offs[t + 2];
-        if (++kt == KT) {
-          kt = 0;
-          ++band;
-        }
-      }
-    }
-    return c;
+  // offsets of tiles t and t + 1 (reloads the window when t + 1 falls outside it)
+  __device__ __forceinline__ void get(uint32_t t, uint32_t& begin, uint32_t& end) {
+    if (t + 1 - base > 63u) load(t);
+    begin = (uint32_t)__builtin_amdgcn_readlane((int)window, (int)(t - base));
+    end = (uint32_t)__builtin_amdgcn_readlane((int)window, (int)(t + 1 - base));
   }
 };
+
+// Words of a tile beyond the R*256 that the register ring stages (a tile denser than the kernel
+// variant was picked for): loaded and extracted on the spot.  Slow, rare, and out of line.
+__device__ __noinline__ void extract_overflow(const uint32_t* words, uint32_t begin, uint32_t end, unsigned char* tile) {
+  const int lane = threadIdx.x & 63;
+  for (uint32_t i = begin + lane * 4; i < end; i += 256) {
+    const u32x4 w = *(const u32x4*)(words + i);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) *(uint16_t*)(tile + ((w[j] & 0xffffu) << 1)) = (uint16_t)(w[j] >> 16);
+  }
+}
 
 template <int NB, int WAVES, int R, int NS>
 __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
@@ -100,12 +78,13 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t g = blockIdx.x * WAVES + wave, G = gridDim.x * WAVES;
-  const uint32_t T = p.out.T;
+  const uint32_t T = p.out.T, KT = p.out.KT;
   const uint32_t t0 = (uint32_t)((uint64_t)g * T / G), t1 = (uint32_t)((uint64_t)(g + 1) * T / G);
   const uint32_t share0 = share_begin(blockIdx.x, T, gridDim.x), share1 = share_begin(blockIdx.x + 1, T, gridDim.x);
   WgReduceLds<NB>* red = (WgReduceLds<NB>*)(lds + WAVES * kWaveLds);
   wg_reduce_init<NB>(red, threadIdx.x, WAVES * 64);
   __syncthreads();  // the only barrier: from here on the waves run independently
+  if (wave == 0) FLS_STAMP(p.out.cnt, blockIdx.x, 0);
   if (t0 >= t1) return;
 
   unsigned char* tile = lds + wave * kWaveLds;
@@ -121,32 +100,45 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 
   XFrags xf;
   xf.init(p.X, p.K, p.out.N, p.out.n0, lane);
-  ChunkWalk<R> walk;
-  walk.init(p.offs, t0, t1, p.out.KT);
-  uint32_t piece_tiles = 0;
+  OffsetWindow win;
+  win.offs = p.offs;
+  win.T = T;
+  win.lane = lane;
+  win.load(t0);
   const unsigned char* frag = tile + ((lane >> 4) * kTileM + (lane & 15)) * 16;
 
-  // gmem2reg: no branch may enclose these loads (the compiler's vmcnt bookkeeping would fall back to
-  // "wait for everything" and the register ring would be lost), so a lane past the end of the
-  // run, or a whole chunk past the end of the wave's tiles, is turned away by the bounds check of
-  // the buffer descriptor instead: it returns 0 and moves no data.
-  auto issue = [&](u32x4(&s)[R], half8(&x)[NB], const Chunk& c) {
+  // Load side: tile ti is the next to be requested; consume side: tile tc is the next to be used.
+  uint32_t ti = t0, kti = t0 % KT;
+  uint32_t tc = t0, ktc = kti, bandc = t0 / KT, piece_tiles = 0;
+
+  // gmem2reg.  No branch may enclose the ring's loads (the compiler's vmcnt bookkeeping would fall
+  // back to "wait for everything" and the ring would be lost), so a lane past the end of the
+  // run, or a tile past the end of the wave's tiles, is turned away by the bounds check of the
+  // buffer descriptor instead: it returns 0 and moves no data.
+  auto issue = [&](u32x4(&s)[R], half8(&x)[NB], uint32_t& begin, uint32_t& end) {
+    win.get(ti, begin, end);
+    uint32_t n = end - begin;
+    if (n > R * 256u) n = R * 256u;
+    if (ti >= t1) n = 0;
     const __amdgpu_buffer_rsrc_t rsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void*)(p.words + c.begin), 0, (int)(c.n * 4u), kBufferFlags);
+        __builtin_amdgcn_make_buffer_rsrc((void*)(p.words + begin), 0, (int)(n * 4u), kBufferFlags);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       if (FLS_ABLATE & 32) s[r] = u32x4{(uint32_t)lane, 1u, 2u, 3u};
       else s[r] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (r * 64 + lane) * 16, 0, kAuxNonTemporal);
     }
-    xf.template load<NB>(x, c.kt);
+    xf.template load<NB>(x, kti);
+    ++ti;
+    if (++kti == KT) kti = 0;
   };
 
   // extract (Alg. 2): value = high half of the word, byte address = 2 * location
-  auto extract = [&](const u32x4(&s)[R], const Chunk& c) {
+  auto extract = [&](const u32x4(&s)[R], uint32_t begin, uint32_t end) {
+    const uint32_t n = end - begin;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const uint32_t q = r * 64 + lane;
-      if (q * 4 < c.n) {
+      if (q * 4 < n) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const uint32_t w = s[r][j];
@@ -155,37 +147,37 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
         }
       }
     }
+    if (n > R * 256u) extract_overflow(p.words, begin + R * 256u, end, tile);
   };
 
-  // smem2tc + rst_smem for a completed tile.  Returns true when the tile ends a band or the wave's run.
-  auto compute = [&](const half8(&x)[NB], const Chunk& c) -> bool {
+  // smem2tc + rst_smem.  All fragment reads are issued first and the re-zeroing right behind
+  // them: the LDS runs a wave's operations in order, so the zeros cannot overtake the reads, and
+  // the MFMAs then wait for the reads only.
+  auto compute = [&](const half8(&x)[NB]) {
+    half8 a[kRowBlocks];
 #pragma unroll
-    for (int h = 0; h < kRowBlocks; h += 4) {  // fragments of four row blocks at a time
-      half8 a[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (FLS_ABLATE & 16) a[j] = x[0];
-        else a[j] = *(const half8*)(frag + (h + j) * 256);
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-          if (FLS_ABLATE & 2) acc[h + j][nb][0] += (float)a[j][0] * (float)x[nb][0];
-          else acc[h + j][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[j], x[nb], acc[h + j][nb], 0, 0, 0);
-        }
-      }
+    for (int rb = 0; rb < kRowBlocks; ++rb) {
+      if (FLS_ABLATE & 16) a[rb] = x[0];
+      else a[rb] = *(const half8*)(frag + rb * 256);
     }
     if (!(FLS_ABLATE & 8)) {
 #pragma unroll
       for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
     }
-    ++piece_tiles;
-    return c.kt + 1 == p.out.KT || c.t + 1 == t1;
+#pragma unroll
+    for (int rb = 0; rb < kRowBlocks; ++rb) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        if (FLS_ABLATE & 2) acc[rb][nb][0] += (float)a[rb][0] * (float)x[nb][0];
+        else acc[rb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[rb], x[nb], acc[rb][nb], 0, 0, 0);
+      }
+    }
   };
 
-  // Hand-over of the piece that just ended in `band` (outside the tile loop on purpose).
+  // Hand-over of the piece that just ended in `band`.
   auto hand_over = [&](uint32_t band) {
+    if (wave == 0 && tc == t1) FLS_STAMP(p.out.cnt, blockIdx.x, 1);
+    if (tc == t1) FLS_STAMP(p.out.cnt, 256 + blockIdx.x, wave);  // debug builds: end of every wave's run
     if (FLS_ABLATE & 1) {
       float sum = 0.f;  // keeps every accumulator alive
 #pragma unroll
@@ -193,17 +185,17 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) sum += acc[rb][nb][0] + acc[rb][nb][1] + acc[rb][nb][2] + acc[rb][nb][3];
       if (sum == 1234.5f) p.out.C[lane] = (_Float16)1;
-    } else if ((FLS_ABLATE & 128) || piece_tiles == p.out.KT) {
+    } else if ((FLS_ABLATE & 128) || piece_tiles == KT) {
       store_band<NB>(p.out, acc, band, lane);  // this wave alone saw the whole band
-      if (!(FLS_ABLATE & 128)) wg_reduce_skip<NB>(red, band - share0 / p.out.KT, lane);
+      if (!(FLS_ABLATE & 128)) wg_reduce_skip<NB>(red, band - share0 / KT, lane);
     } else {
-      const uint32_t band_lo = band * p.out.KT;
+      const uint32_t band_lo = band * KT;
       const uint32_t lo = share0 > band_lo ? share0 : band_lo;
-      const uint32_t hi = share1 < band_lo + p.out.KT ? share1 : band_lo + p.out.KT;
-      const uint32_t seq = band - share0 / p.out.KT;
+      const uint32_t hi = share1 < band_lo + KT ? share1 : band_lo + KT;
+      const uint32_t seq = band - share0 / KT;
       if (wg_reduce_add<NB>(red, acc, seq, piece_tiles, hi - lo, lane))
-        finish_band<NB>(red, p.out.C, p.out.parts, p.out.cnt, p.out.M, p.out.N, p.out.n0, p.out.KT, p.out.T, seq, band, lo,
-                        hi, share0, blockIdx.x, gridDim.x, (FLS_ABLATE & 64) != 0);
+        finish_band<NB>(red, p.out.C, p.out.parts, p.out.cnt, p.out.M, p.out.N, p.out.n0, KT, T, seq, band, lo, hi, share0,
+                        blockIdx.x, gridDim.x, (FLS_ABLATE & 64) != 0);
     }
     piece_tiles = 0;
 #pragma unroll
@@ -212,73 +204,42 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
       for (int nb = 0; nb < NB; ++nb) acc[rb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
   };
 
-  // Register ring of NS chunks in flight.  A stage is refilled as soon as its words are in LDS,
-  // before the MFMA work of its tile, so loads lead their use by NS - 1 tiles of work.  The tile
-  // loop is straight-line in its global loads - every stage issues the same number, none under
-  // a condition - which is what lets the compiler wait for exactly the stage it needs
-  // (s_waitcnt vmcnt(n) with n = loads issued since); it is left only when a piece ends.
+  // Register ring of NS tiles in flight.  A stage is refilled as soon as its words are in LDS,
+  // before the MFMA work of its tile, so loads lead their use by NS - 1 tiles of work.  The loop
+  // is straight-line in the ring's loads - every step issues the same number, none under a
+  // condition - which lets the compiler wait for exactly the stage it needs
+  // (s_waitcnt vmcnt(n), n = loads issued since).
   u32x4 s[NS][R];
   half8 x[NS][NB];
-  Chunk c[NS];
+  uint32_t sb[NS], se[NS];  // word range of the tile each stage holds
 #pragma unroll
-  for (int i = 0; i < NS; ++i) {
-    c[i] = walk.next();
-    issue(s[i], x[i], c[i]);
-  }
-  uint32_t pos = 0, end_band = 0;
+  for (int i = 0; i < NS; ++i) issue(s[i], x[i], sb[i], se[i]);
 
-#define FLS_RING_STEP(i)                                  \
-  if constexpr ((i) < NS) {                               \
-    if (!c[i].valid) goto run_done;                       \
-    const Chunk cur = c[i];                               \
-    extract(s[i], cur);                                   \
-    half8 xc[NB];                                         \
-    _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) xc[nb] = x[i][nb]; \
-    c[i] = walk.next();                                   \
-    issue(s[i], x[i], c[i]);                              \
-    if (cur.last && compute(xc, cur)) {                   \
-      pos = (i);                                          \
-      end_band = cur.band;                                \
-      goto piece_done;                                    \
-    }                                                     \
-  }
-
-  for (;;) {
-    for (;;) {
-      FLS_RING_STEP(0)
-      FLS_RING_STEP(1)
-      FLS_RING_STEP(2)
-      FLS_RING_STEP(3)
-    }
-  piece_done:
-    // bring the oldest stage to position 0 so that the tile loop can be entered from its top
-    for (uint32_t k = (pos + 1) % NS; k > 0; --k) {
-      u32x4 ts[R];
-      half8 tx[NB];
-      const Chunk tc = c[0];
+  auto step = [&](u32x4(&ss)[R], half8(&sx)[NB], uint32_t& b, uint32_t& e) {
+    extract(ss, b, e);
+    half8 xc[NB];
 #pragma unroll
-      for (int r = 0; r < R; ++r) ts[r] = s[0][r];
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) tx[nb] = x[0][nb];
-#pragma unroll
-      for (int i = 0; i + 1 < NS; ++i) {
-        c[i] = c[i + 1];
-#pragma unroll
-        for (int r = 0; r < R; ++r) s[i][r] = s[i + 1][r];
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) x[i][nb] = x[i + 1][nb];
+    for (int nb = 0; nb < NB; ++nb) xc[nb] = sx[nb];
+    issue(ss, sx, b, e);
+    compute(xc);
+    ++piece_tiles;
+    ++tc;
+    if (++ktc == KT || tc == t1) {
+      hand_over(bandc);
+      if (ktc == KT) {
+        ktc = 0;
+        ++bandc;
       }
-      c[NS - 1] = tc;
-#pragma unroll
-      for (int r = 0; r < R; ++r) s[NS - 1][r] = ts[r];
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) x[NS - 1][nb] = tx[nb];
     }
-    hand_over(end_band);
+  };
+
+  while (tc + NS <= t1) {
+#pragma unroll
+    for (int i = 0; i < NS; ++i) step(s[i], x[i], sb[i], se[i]);
   }
-run_done:
-  return;
-#undef FLS_RING_STEP
+#pragma unroll
+  for (int i = 0; i < NS - 1; ++i)
+    if (tc < t1) step(s[i], x[i], sb[i], se[i]);
 }
 
 // ---------------------------------------------------------------- host launcher
@@ -329,7 +290,8 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
   p.out.N = a.N;
   p.out.KT = a.K / kTileK;
   const int grid = a.num_cus < kMaxGrid ? a.num_cus : kMaxGrid;
-  // words staged per chunk: the smallest variant that takes the densest tile in one piece
+  // rounds of 256 words staged per tile: the smallest variant that holds the densest tile
+  // (a denser tile is still handled, through a slow path)
   int R = 8;
   if (a.max_tile_words <= 2 * 256) R = 2;
   else if (a.max_tile_words <= 4 * 256) R = 4;
