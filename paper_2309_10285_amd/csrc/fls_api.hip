@@ -94,11 +94,11 @@ int check_mm_args(const void* W, const void* X, void* C, int64_t M, int64_t K, i
   return FLS_OK;
 }
 
-// Workspace: a fixed 4 MiB area of u32 arrival counters, one per row band (M * K < 2^32 and
-// K >= 32 bound the bands by 2^20), then the split-K partial slots (fp32).  The counter area has
-// the same place for every shape, so partial sums of one call can never be read as counters by
-// the next.
+// Workspace: a fixed 4 MiB control area (one u32 flag per workgroup and an error word; the rest
+// is spare), then the split-K partial slots (fp32).  The control area has the same place for
+// every shape, so partial sums of one call can never be read as flags by the next.
 constexpr size_t kCounterAreaBytes = (size_t)4 << 20;
+uint32_t g_epoch = 0;  // launches since the workspace was registered; a flag equal to it is current
 void workspace_layout(int64_t N, size_t* total) {
   *total = kCounterAreaBytes + fls::parts_floats((uint32_t)N) * sizeof(float);
 }
@@ -179,6 +179,7 @@ int fls_set_workspace(void* ws_dev, size_t bytes, fls_stream_t stream) {
   std::lock_guard<std::mutex> lk(g_mu);
   g_ws = ws_dev;
   g_ws_bytes = bytes;
+  g_epoch = 0;
   return FLS_OK;
 }
 
@@ -195,12 +196,15 @@ int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int6
   size_t need;
   workspace_layout(N, &need);
   void* ws;
+  uint32_t epoch0;
   BlobInfo info;
   bool known;
   {
     std::lock_guard<std::mutex> lk(g_mu);
     if (!g_ws || g_ws_bytes < need) return FLS_EWORKSPACE;
     ws = g_ws;
+    epoch0 = g_epoch + 1;  // one launch per group of 64 columns
+    g_epoch += (uint32_t)((N + 63) / 64);
     auto it = g_blobs.find(Wc_dev);
     known = it != g_blobs.end();
     if (known) info = it->second;
@@ -225,7 +229,8 @@ int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int6
   a.words = a.offs + info.n_off;
   a.X = (const _Float16*)X_dev;
   a.C = (_Float16*)C_dev;
-  a.cnt = (uint32_t*)ws;
+  a.flags = (uint32_t*)ws;
+  a.epoch0 = epoch0;
   a.parts = (float*)((unsigned char*)ws + kCounterAreaBytes);
   a.M = (uint32_t)M;
   a.K = (uint32_t)K;
@@ -242,10 +247,13 @@ int fls_dense_gemm(const void* W_dev, const void* X_dev, void* C_dev, int64_t M,
   size_t need;
   workspace_layout(N, &need);
   void* ws;
+  uint32_t epoch0;
   {
     std::lock_guard<std::mutex> lk(g_mu);
     if (!g_ws || g_ws_bytes < need) return FLS_EWORKSPACE;
     ws = g_ws;
+    epoch0 = g_epoch + 1;
+    g_epoch += (uint32_t)((N + 63) / 64);
   }
   const int cus = num_cus();
   if (cus <= 0) return FLS_EHIP;
@@ -253,7 +261,8 @@ int fls_dense_gemm(const void* W_dev, const void* X_dev, void* C_dev, int64_t M,
   a.W = (const _Float16*)W_dev;
   a.X = (const _Float16*)X_dev;
   a.C = (_Float16*)C_dev;
-  a.cnt = (uint32_t*)ws;
+  a.flags = (uint32_t*)ws;
+  a.epoch0 = epoch0;
   a.parts = (float*)((unsigned char*)ws + kCounterAreaBytes);
   a.M = (uint32_t)M;
   a.K = (uint32_t)K;

@@ -53,6 +53,7 @@ __global__ __launch_bounds__(WAVES * 64) void dense_kernel(DenseParams p) {
   };
 
   uint32_t piece_tiles = 0;
+  HandoverState hs;
   auto consume = [&](half8(&a)[kRowBlocks], half8(&x)[NB], uint32_t t) {
     const uint32_t band = t / KT, kt = t - band * KT;
 #pragma unroll
@@ -61,23 +62,8 @@ __global__ __launch_bounds__(WAVES * 64) void dense_kernel(DenseParams p) {
       for (int nb = 0; nb < NB; ++nb) acc[rb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[rb], x[nb], acc[rb][nb], 0, 0, 0);
     ++piece_tiles;
     if (kt + 1 == KT || t + 1 == t1) {
-      if (piece_tiles == KT) {
-        store_band<NB>(p.out, acc, band, lane);
-        wg_reduce_skip<NB>(red, band - share0 / KT, lane);
-      } else {
-        const uint32_t band_lo = band * KT;
-        const uint32_t lo = share0 > band_lo ? share0 : band_lo;
-        const uint32_t hi = share1 < band_lo + KT ? share1 : band_lo + KT;
-        const uint32_t seq = band - share0 / KT;
-        if (wg_reduce_add<NB>(red, acc, seq, piece_tiles, hi - lo, lane))
-          finish_band<NB>(red, p.out.C, p.out.parts, p.out.cnt, p.out.M, p.out.N, p.out.n0, KT, p.out.T, seq, band, lo, hi,
-                          share0, blockIdx.x, gridDim.x, false);
-      }
+      hand_over_piece<NB>(p.out, red, acc, hs, band, piece_tiles, share0, share1, blockIdx.x, lane, false);
       piece_tiles = 0;
-#pragma unroll
-      for (int rb = 0; rb < kRowBlocks; ++rb)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) acc[rb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
     }
   };
 
@@ -91,6 +77,7 @@ __global__ __launch_bounds__(WAVES * 64) void dense_kernel(DenseParams p) {
     consume(ab, xb, t + 1);
     issue(ab, xb, t + 3);
   }
+  hand_over_finish<NB>(p.out, acc, hs, blockIdx.x, gridDim.x, lane);
 }
 
 template <int NB, int WAVES>
@@ -114,13 +101,14 @@ hipError_t launch_dense(const DenseLaunch& a, hipStream_t stream) {
   p.out.T = (a.M / kTileM) * (a.K / kTileK);
   p.out.C = a.C;
   p.out.parts = a.parts;
-  p.out.cnt = a.cnt;
+  p.out.flags = a.flags;
   p.out.M = a.M;
   p.out.N = a.N;
   p.out.KT = a.K / kTileK;
-  const int grid = a.num_cus < kMaxGrid ? a.num_cus : kMaxGrid;
+  const int grid = pick_grid(a.M / kTileM, a.num_cus);
   for (uint32_t n0 = 0; n0 < a.N; n0 += 64) {
     p.out.n0 = n0;
+    p.out.epoch = a.epoch0 + n0 / 64;
     const uint32_t ncols = a.N - n0 < 64 ? a.N - n0 : 64;
     hipError_t e;
     if (ncols <= 16) e = launch_dense_variant<1, 8>(p, grid, stream);

@@ -7,7 +7,7 @@
 namespace fls {
 
 // Debug builds only (-DFLS_TRACE): 100 MHz timestamps of the hand-over steps, kept in the unused
-// tail of the counter area: cnt[65536 + 16 * workgroup + k].
+// tail of the flag area: flags[65536 + 16 * workgroup + k].
 #ifdef FLS_TRACE
 #define FLS_STAMP(cnt, wg, k)                                                             \
   do {                                                                                    \
@@ -42,18 +42,19 @@ constexpr int kAuxCoherent = 16;            // sc1: device scope - through to me
 // waves of a workgroup.  Partial results of one band meet in two steps:
 //   1. inside a workgroup, in LDS (wg_reduce): waves add their accumulators to one of two band
 //      slots and count their tiles; the wave that completes the workgroup's share takes the sum;
-//   2. between workgroups, in HBM (band_handover): that wave stores the sum to its workgroup's
-//      slot, counts the share in the band's arrival counter, and the workgroup that completes
-//      the band adds up the slots in workgroup order and writes fp16 C.
-// No floating-point atomics touch HBM; counters return to zero, so the workspace is reusable.
+//   2. between workgroups, in HBM: that wave stores the sum to its workgroup's slot and later
+//      raises the workgroup's flag; the workgroup that owns the band adds up the slots in
+//      workgroup order and writes fp16 C (see "between workgroups" below).
+// No floating-point atomics touch HBM.
 struct OutParams {
   _Float16* C;      // column-major M x N
-  float* parts;     // [workgroup][2][NB * 2048] fp32 partial sums in accumulator order
-  uint32_t* cnt;    // [band] arrived K tiles, all zero between calls
+  float* parts;     // [workgroup][NB * 2048] fp32 partial sums in accumulator order
+  uint32_t* flags;  // [workgroup] epoch of the last published partial sum; [kMaxGrid] error word
   uint32_t M, N;    // N = columns of the whole problem
   uint32_t n0;      // first column of this launch's column group
   uint32_t KT;      // K tiles per band
   uint32_t T;       // tiles in total
+  uint32_t epoch;   // this launch's number (never 0)
 };
 
 // First tile of workgroup q's share when T tiles are cut over P workgroups.
@@ -167,72 +168,77 @@ __device__ __forceinline__ void wg_reduce_skip(WgReduceLds<NB>* red, uint32_t se
   if (lane == 0) __hip_atomic_store(&red->gen[s], turn + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
 
-// The between-workgroups step, run by the one wave per (workgroup, band) that wg_reduce picked.
-// acc is the workgroup's sum over tiles [lo, hi) of `band`; share0 is the first tile of the
-// workgroup's share, wg its index, P the number of workgroups.
+// ---- between workgroups
+//
+// A band that is cut between workgroups is finished by its owner: the workgroup whose share holds
+// the band's first tile.  The owner's piece of the band is the last thing in its share, so its
+// sum is still in registers when its run ends.  Every other workgroup that holds tiles of the
+// band stores its sum to its slot when its piece ends (plain write-through stores, nothing waits
+// for them) and publishes the slot when its own run ends, by writing the call's epoch number to
+// its flag after the stores were acknowledged.  The owner then polls those flags, adds the slots
+// in workgroup order (so the result does not depend on timing) and writes fp16 C.
+//
+// Partial sums cross between the L2 caches of different XCDs: they are written through to memory
+// and read past the caches access by access (sc1 on the instruction), so no cache-wide write-back
+// or invalidate - what a device-scope fence costs - is needed.  Flags compare against an epoch
+// that the host advances with every launch, so nothing has to be cleared between calls.
+//
+// A workgroup publishes before it polls, and only polls workgroups of higher index, so the wait
+// ends as soon as those workgroups have run; the spin is bounded all the same.
+constexpr uint32_t kSpinLimit = 1u << 20;
+
 template <int NB>
-__device__ __forceinline__ void band_handover(const OutParams& o, float4v (&acc)[kRowBlocks][NB], uint32_t band,
-                                              uint32_t lo, uint32_t hi, uint32_t share0, uint32_t wg, uint32_t P,
+__device__ __forceinline__ void store_partial(const OutParams& o, const float4v (&acc)[kRowBlocks][NB], uint32_t wg,
                                               int lane) {
-  const uint32_t band_lo = band * o.KT, band_hi = band_lo + o.KT;
-  if (lo == band_lo && hi == band_hi) {
-    store_band<NB>(o, acc, band, lane);  // the workgroup saw the whole band
-    return;
-  }
-  // slot 0: the band in which the workgroup's share begins; slot 1: a later band (only its last,
-  // cut-off band can be partial, so each slot is used at most once per call)
-  const uint32_t my_slot = share0 < band_lo ? 1u : 0u;
-  // Partial sums cross between the L2 caches of different XCDs.  They are written through to
-  // memory and read past the caches access by access (sc1 on the instruction), so that no
-  // cache-wide write-back or invalidate - what a device-scope fence costs - is needed: waiting
-  // for the stores to be acknowledged orders them before the counter.  A slot is kept as
-  // [column block][row block][lane] float4, 1 KB per instruction.
-  constexpr int kSlotBytes = NB * kAccPerBlock * 4;
-  FLS_STAMP(o.cnt, wg, 2 + 6 * my_slot);
-  {
-    const __amdgpu_buffer_rsrc_t mine = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)(o.parts + ((size_t)wg * 2 + my_slot) * (NB * kAccPerBlock)), 0, kSlotBytes, kBufferFlags);
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-      for (int rb = 0; rb < kRowBlocks; ++rb)
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[rb][nb]), mine,
-                                               ((nb * kRowBlocks + rb) * 64 + lane) * 16, 0, kAuxCoherent);
-  }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // s_waitcnt vmcnt(0): the stores are done
-  FLS_STAMP(o.cnt, wg, 3 + 6 * my_slot);
-  uint32_t old = 0;
-  if (lane == 0) old = __hip_atomic_fetch_add(o.cnt + band, hi - lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  old = __builtin_amdgcn_readfirstlane(old);
-  FLS_STAMP(o.cnt, wg, 4 + 6 * my_slot);
-  if (old + (hi - lo) != o.KT) return;
-  // last arrival: every share of this band is stored; add them in workgroup order.  The loads
-  // of up to kBatch shares are all issued before the first is used: each is a trip to memory,
-  // and this code runs when the kernel is about to end, with nothing left to hide it behind.
-  constexpr int kBatch = NB == 1 ? 4 : (NB == 2 ? 2 : 1);
-  uint32_t q = (uint32_t)((uint64_t)band_lo * P / o.T);
-  while (q > 0 && share_begin(q, o.T, P) > band_lo) --q;
+  const __amdgpu_buffer_rsrc_t mine = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(o.parts + (size_t)wg * (NB * kAccPerBlock)), 0, NB * kAccPerBlock * 4, kBufferFlags);
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-    for (int rb = 0; rb < kRowBlocks; ++rb) acc[rb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
+    for (int rb = 0; rb < kRowBlocks; ++rb)
+      __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[rb][nb]), mine,
+                                             ((nb * kRowBlocks + rb) * 64 + lane) * 16, 0, kAuxCoherent);
+}
+
+// By the wave that called store_partial, once its run is over.
+__device__ __forceinline__ void publish_partial(const OutParams& o, uint32_t wg, int lane) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // s_waitcnt vmcnt(0): the stores are acknowledged
+  if (lane == 0) __hip_atomic_store(o.flags + wg, o.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// acc holds the owner's own sum for `band`; adds the other workgroups' and writes C.
+template <int NB>
+__device__ __forceinline__ void owner_finish(const OutParams& o, float4v (&acc)[kRowBlocks][NB], uint32_t band,
+                                             uint32_t wg, uint32_t P, int lane) {
+  const uint32_t band_hi = (band + 1) * o.KT;
+  for (uint32_t q = wg + 1; q < P && share_begin(q, o.T, P) < band_hi; ++q) {
+    if (share_begin(q + 1, o.T, P) == share_begin(q, o.T, P)) continue;  // empty share: no contribution
+    uint32_t spins = 0;
+    while (__hip_atomic_load(o.flags + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != o.epoch) {
+      __builtin_amdgcn_s_sleep(8);
+      if (++spins == kSpinLimit) {  // never seen; gives up rather than hang, and says so
+        if (lane == 0) __hip_atomic_store(o.flags + kMaxGrid, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        break;
+      }
+    }
+  }
+  // The loads of up to kBatch slots are all issued before the first is used: each is a trip to
+  // memory, and this runs when the kernel is about to end, with nothing left to hide it behind.
+  constexpr int kBatch = NB == 1 ? 4 : (NB == 2 ? 2 : 1);
+  uint32_t q = wg + 1;
   while (q < P && share_begin(q, o.T, P) < band_hi) {
     u32x4 v[kBatch][NB][kRowBlocks];
 #pragma unroll
     for (int j = 0; j < kBatch; ++j) {
-      // next share that overlaps the band; past the last one the descriptor is empty and reads 0
-      uint32_t qb = 0, qe = 0;
+      // next workgroup with tiles of the band; past the last one the descriptor is empty and reads 0
       bool found = false;
       while (!found && q < P && share_begin(q, o.T, P) < band_hi) {
-        qb = share_begin(q, o.T, P);
-        qe = share_begin(q + 1, o.T, P);
-        found = qe > band_lo && qe != qb;
+        found = share_begin(q + 1, o.T, P) != share_begin(q, o.T, P);
         if (!found) ++q;
       }
-      const uint32_t slot = qb < band_lo ? 1u : 0u;
-      const __amdgpu_buffer_rsrc_t src = __builtin_amdgcn_make_buffer_rsrc(
-          (void*)(o.parts + ((size_t)(found ? q : 0u) * 2 + slot) * (NB * kAccPerBlock)), 0, found ? kSlotBytes : 0,
-          kBufferFlags);
+      const __amdgpu_buffer_rsrc_t src =
+          __builtin_amdgcn_make_buffer_rsrc((void*)(o.parts + (size_t)(found ? q : 0u) * (NB * kAccPerBlock)), 0,
+                                            found ? NB * kAccPerBlock * 4 : 0, kBufferFlags);
       if (found) ++q;
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
@@ -247,33 +253,58 @@ __device__ __forceinline__ void band_handover(const OutParams& o, float4v (&acc)
 #pragma unroll
         for (int rb = 0; rb < kRowBlocks; ++rb) acc[rb][nb] += __builtin_bit_cast(float4v, v[j][nb][rb]);
   }
-  FLS_STAMP(o.cnt, wg, 5 + 6 * my_slot);
   store_band<NB>(o, acc, band, lane);
-  if (lane == 0) __hip_atomic_store(o.cnt + band, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  FLS_STAMP(o.cnt, wg, 6 + 6 * my_slot);
 }
 
-// Everything the picked wave does after its own contribution, kept out of line: it runs at most
-// twice per workgroup and call, and inlined into the tile loop it would cost the loop its registers.
+// What a wave carries from the tile loop to the end of its run.
+struct HandoverState {
+  bool publish = false;  // it stored its workgroup's partial sum and still has to publish it
+  bool own = false;      // it holds the owner's sum of band own_band in its accumulators
+  uint32_t own_band = 0;
+};
+
+// Hand-over of a wave's piece (tiles of one band), inside the tile loop: LDS work and, at most,
+// stores that nothing waits for.  `tiles` = tiles in the piece, [share0, share1) = the
+// workgroup's share.  Leaves acc cleared for the next band unless the wave became an owner.
 template <int NB>
-__device__ __noinline__ void finish_band(WgReduceLds<NB>* red, _Float16* C, float* parts, uint32_t* cnt, uint32_t M,
-                                         uint32_t N, uint32_t n0, uint32_t KT, uint32_t T, uint32_t seq, uint32_t band,
-                                         uint32_t lo, uint32_t hi, uint32_t share0, uint32_t wg, uint32_t P,
-                                         bool local_only) {
-  const int lane = threadIdx.x & 63;
-  OutParams o;
-  o.C = C;
-  o.parts = parts;
-  o.cnt = cnt;
-  o.M = M;
-  o.N = N;
-  o.n0 = n0;
-  o.KT = KT;
-  o.T = T;
-  float4v acc[kRowBlocks][NB];
-  wg_reduce_take<NB>(red, acc, seq, lane);
-  if (local_only) store_band<NB>(o, acc, band, lane);
-  else band_handover<NB>(o, acc, band, lo, hi, share0, wg, P, lane);
+__device__ __forceinline__ void hand_over_piece(const OutParams& o, WgReduceLds<NB>* red, float4v (&acc)[kRowBlocks][NB],
+                                                HandoverState& st, uint32_t band, uint32_t tiles, uint32_t share0,
+                                                uint32_t share1, uint32_t wg, int lane, bool local_only) {
+  const uint32_t seq = band - share0 / o.KT;
+  if (tiles == o.KT) {
+    store_band<NB>(o, acc, band, lane);  // this wave alone saw the whole band
+    wg_reduce_skip<NB>(red, seq, lane);
+  } else {
+    const uint32_t band_lo = band * o.KT, band_hi = band_lo + o.KT;
+    const uint32_t lo = share0 > band_lo ? share0 : band_lo;
+    const uint32_t hi = share1 < band_hi ? share1 : band_hi;
+    if (wg_reduce_add<NB>(red, acc, seq, tiles, hi - lo, lane)) {
+      wg_reduce_take<NB>(red, acc, seq, lane);  // acc = the workgroup's sum over [lo, hi)
+      if ((lo == band_lo && hi == band_hi) || local_only) {
+        store_band<NB>(o, acc, band, lane);
+      } else if (lo == band_lo) {
+        st.own = true;  // the share ends inside this band: nothing follows, keep the sum
+        st.own_band = band;
+      } else {
+        store_partial<NB>(o, acc, wg, lane);
+        st.publish = true;
+      }
+    }
+  }
+  if (!st.own) {
+#pragma unroll
+    for (int rb = 0; rb < kRowBlocks; ++rb)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) acc[rb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
+  }
+}
+
+// After the tile loop.
+template <int NB>
+__device__ __forceinline__ void hand_over_finish(const OutParams& o, float4v (&acc)[kRowBlocks][NB],
+                                                 const HandoverState& st, uint32_t wg, uint32_t P, int lane) {
+  if (st.publish) publish_partial(o, wg, lane);
+  if (st.own) owner_finish<NB>(o, acc, st.own_band, wg, P, lane);
 }
 
 // B operand fragments (X) of one K tile, straight from global memory (they stay in L2): lane l

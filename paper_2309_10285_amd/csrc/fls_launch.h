@@ -11,7 +11,8 @@ struct SpmmLaunch {
   const _Float16* X;
   _Float16* C;
   float* parts;
-  uint32_t* cnt;
+  uint32_t* flags;
+  uint32_t epoch0;  // launch number of the first column group (the next groups count on)
   uint32_t M, K, N;
   uint32_t max_tile_words;
   int num_cus;
@@ -22,7 +23,8 @@ struct DenseLaunch {
   const _Float16* X;
   _Float16* C;
   float* parts;
-  uint32_t* cnt;
+  uint32_t* flags;
+  uint32_t epoch0;  // launch number of the first column group (the next groups count on)
   uint32_t M, K, N;
   int num_cus;
 };
@@ -38,8 +40,23 @@ struct CompressLaunch {
 // blocks of 16.
 inline uint32_t group_blocks(uint32_t ncols) { return ncols <= 16 ? 1u : (ncols <= 32 ? 2u : 4u); }
 constexpr uint32_t kMaxWorkgroups = 512;    // must equal fls::kMaxGrid of the device code
-// fp32 values of the split-K partial slots: [workgroup][2][column blocks][128 x 16]
-inline size_t parts_floats(uint32_t N) { return (size_t)kMaxWorkgroups * 2 * group_blocks(N < 64 ? N : 64) * 2048; }
+// fp32 values of the split-K partial slots: [workgroup][column blocks][128 x 16]
+inline size_t parts_floats(uint32_t N) { return (size_t)kMaxWorkgroups * group_blocks(N < 64 ? N : 64) * 2048; }
+
+// Number of workgroups for a matrix of `bands` row bands on `cus` compute units (one workgroup
+// per CU at most).  A count of the form bands * k gives every band to exactly k workgroups: with
+// k = 1 no partial sum ever crosses between workgroups, and the serial hand-over chain at the end
+// of the kernel (store, count, read back: a few microseconds with the whole chip waiting) goes
+// away.  That is worth leaving up to a fifth of the CUs without a workgroup: the kernel is paced by
+// HBM, not by the CUs.  Otherwise every CU gets an equal share, cut wherever it falls.
+inline int pick_grid(uint32_t bands, int cus) {
+  if (cus > (int)kMaxWorkgroups) cus = (int)kMaxWorkgroups;
+  if ((int)bands <= cus) {
+    const int aligned = (int)bands * (cus / (int)bands);
+    if (aligned * 5 >= cus * 4) return aligned;
+  }
+  return cus;
+}
 
 hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream);
 hipError_t launch_dense(const DenseLaunch& a, hipStream_t stream);

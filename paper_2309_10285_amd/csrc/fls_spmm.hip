@@ -84,7 +84,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   WgReduceLds<NB>* red = (WgReduceLds<NB>*)(lds + WAVES * kWaveLds);
   wg_reduce_init<NB>(red, threadIdx.x, WAVES * 64);
   __syncthreads();  // the only barrier: from here on the waves run independently
-  if (wave == 0) FLS_STAMP(p.out.cnt, blockIdx.x, 0);
+  if (wave == 0) FLS_STAMP(p.out.flags, blockIdx.x, 0);
   if (t0 >= t1) return;
 
   unsigned char* tile = lds + wave * kWaveLds;
@@ -175,9 +175,9 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   };
 
   // Hand-over of the piece that just ended in `band`.
+  HandoverState hs;
   auto hand_over = [&](uint32_t band) {
-    if (wave == 0 && tc == t1) FLS_STAMP(p.out.cnt, blockIdx.x, 1);
-    if (tc == t1) FLS_STAMP(p.out.cnt, 256 + blockIdx.x, wave);  // debug builds: end of every wave's run
+    if (tc == t1) FLS_STAMP(p.out.flags, 256 + blockIdx.x, wave);  // debug builds: end of every wave's run
     if (FLS_ABLATE & 1) {
       float sum = 0.f;  // keeps every accumulator alive
 #pragma unroll
@@ -185,23 +185,18 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) sum += acc[rb][nb][0] + acc[rb][nb][1] + acc[rb][nb][2] + acc[rb][nb][3];
       if (sum == 1234.5f) p.out.C[lane] = (_Float16)1;
-    } else if ((FLS_ABLATE & 128) || piece_tiles == KT) {
-      store_band<NB>(p.out, acc, band, lane);  // this wave alone saw the whole band
-      if (!(FLS_ABLATE & 128)) wg_reduce_skip<NB>(red, band - share0 / KT, lane);
+    } else if (FLS_ABLATE & 128) {
+      store_band<NB>(p.out, acc, band, lane);
     } else {
-      const uint32_t band_lo = band * KT;
-      const uint32_t lo = share0 > band_lo ? share0 : band_lo;
-      const uint32_t hi = share1 < band_lo + KT ? share1 : band_lo + KT;
-      const uint32_t seq = band - share0 / KT;
-      if (wg_reduce_add<NB>(red, acc, seq, piece_tiles, hi - lo, lane))
-        finish_band<NB>(red, p.out.C, p.out.parts, p.out.cnt, p.out.M, p.out.N, p.out.n0, KT, T, seq, band, lo, hi, share0,
-                        blockIdx.x, gridDim.x, (FLS_ABLATE & 64) != 0);
+      hand_over_piece<NB>(p.out, red, acc, hs, band, piece_tiles, share0, share1, blockIdx.x, lane, (FLS_ABLATE & 64) != 0);
     }
     piece_tiles = 0;
+    if (FLS_ABLATE & (1 | 128)) {
 #pragma unroll
-    for (int rb = 0; rb < kRowBlocks; ++rb)
+      for (int rb = 0; rb < kRowBlocks; ++rb)
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) acc[rb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
+        for (int nb = 0; nb < NB; ++nb) acc[rb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
+    }
   };
 
   // Register ring of NS tiles in flight.  A stage is refilled as soon as its words are in LDS,
@@ -240,6 +235,8 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 #pragma unroll
   for (int i = 0; i < NS - 1; ++i)
     if (tc < t1) step(s[i], x[i], sb[i], se[i]);
+  hand_over_finish<NB>(p.out, acc, hs, blockIdx.x, gridDim.x, lane);
+  if (wave == 0) FLS_STAMP(p.out.flags, blockIdx.x, 2);
 }
 
 // ---------------------------------------------------------------- host launcher
@@ -285,11 +282,11 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
   p.out.T = (a.M / kTileM) * (a.K / kTileK);
   p.out.C = a.C;
   p.out.parts = a.parts;
-  p.out.cnt = a.cnt;
+  p.out.flags = a.flags;
   p.out.M = a.M;
   p.out.N = a.N;
   p.out.KT = a.K / kTileK;
-  const int grid = a.num_cus < kMaxGrid ? a.num_cus : kMaxGrid;
+  const int grid = pick_grid(a.M / kTileM, a.num_cus);
   // rounds of 256 words staged per tile: the smallest variant that holds the densest tile
   // (a denser tile is still handled, through a slow path)
   int R = 8;
@@ -298,6 +295,7 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
   else if (a.max_tile_words <= 6 * 256) R = 6;
   for (uint32_t n0 = 0; n0 < a.N; n0 += 64) {
     p.out.n0 = n0;
+    p.out.epoch = a.epoch0 + n0 / 64;
     const uint32_t ncols = a.N - n0 < 64 ? a.N - n0 : 64;
     hipError_t e;
     if (ncols <= 16) e = launch_r<1, FLS_WAVES>(R, p, grid, stream);

@@ -32,10 +32,10 @@ def test_sizes_and_bounds(fls):
     # closed forms: header + offsets (round_up(tiles + 4, 16) u32) + 4 B per element
     assert fls.fls_compress_bound(128, 32) == 64 + 4 * 16 + 4 * 4096
     assert fls.fls_compress_bound(1024, 1024) == 64 + 4 * 272 + 4 * 1024 * 1024
-    # 4 MiB of band counters + [512 workgroups][2 slots][column blocks][128 x 16] fp32
-    assert fls.fls_workspace_bytes(1024, 1024, 8) == (4 << 20) + 512 * 2 * 1 * 2048 * 4
-    assert fls.fls_workspace_bytes(1024, 1024, 17) == (4 << 20) + 512 * 2 * 2 * 2048 * 4
-    assert fls.fls_workspace_bytes(1024, 1024, 256) == (4 << 20) + 512 * 2 * 4 * 2048 * 4
+    # 4 MiB control area + [512 workgroups][column blocks][128 x 16] fp32
+    assert fls.fls_workspace_bytes(1024, 1024, 8) == (4 << 20) + 512 * 1 * 2048 * 4
+    assert fls.fls_workspace_bytes(1024, 1024, 17) == (4 << 20) + 512 * 2 * 2048 * 4
+    assert fls.fls_workspace_bytes(1024, 1024, 256) == (4 << 20) + 512 * 4 * 2048 * 4
     assert fls.fls_workspace_bytes(1000, 1024, 8) == 0 and fls.fls_workspace_bytes(1024, 1024, 257) == 0
     assert fls.TILE_M == 128 and fls.TILE_K == 32
 
