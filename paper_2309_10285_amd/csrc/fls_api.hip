@@ -33,7 +33,8 @@ inline uint64_t round_up(uint64_t v, uint64_t m) { return (v + m - 1) / m * m; }
 bool shape_ok(int64_t M, int64_t K) {
   if (M <= 0 || K <= 0) return false;
   if (M % FLS_TILE_M != 0 || K % FLS_TILE_K != 0) return false;
-  if (M > 0x7fffffffll || K > 0x7fffffffll) return false;
+  // K: byte offsets inside a 128-row band (and inside X) are 32 bit
+  if (M > 0x7fffffffll || K > (1ll << 23)) return false;
   // word offsets are 32 bit: the densest possible blob must stay below 2^32 words
   if ((uint64_t)M * (uint64_t)K >= (1ull << 32)) return false;
   return true;
@@ -203,8 +204,8 @@ int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int6
     std::lock_guard<std::mutex> lk(g_mu);
     if (!g_ws || g_ws_bytes < need) return FLS_EWORKSPACE;
     ws = g_ws;
-    epoch0 = g_epoch + 1;  // one launch per group of 64 columns
-    g_epoch += (uint32_t)((N + 63) / 64);
+    epoch0 = g_epoch + 1;  // one launch per column group
+    g_epoch += fls::column_groups((uint32_t)N);
     auto it = g_blobs.find(Wc_dev);
     known = it != g_blobs.end();
     if (known) info = it->second;
@@ -253,7 +254,7 @@ int fls_dense_gemm(const void* W_dev, const void* X_dev, void* C_dev, int64_t M,
     if (!g_ws || g_ws_bytes < need) return FLS_EWORKSPACE;
     ws = g_ws;
     epoch0 = g_epoch + 1;
-    g_epoch += (uint32_t)((N + 63) / 64);
+    g_epoch += fls::column_groups((uint32_t)N);
   }
   const int cus = num_cus();
   if (cus <= 0) return FLS_EHIP;

@@ -1,7 +1,7 @@
 // fls_dense_gemm: the dense fp16 baseline C = W . X for skinny N on gfx950, built like the sparse
 // kernel minus its sparse stages (the paper pairs every SpMM point with a dense GEMM, Sec. 6):
-// every wave owns a contiguous run of 128 x 32 tiles of W, loads the MFMA A fragments straight
-// from HBM (a lane's 8 consecutive k are one 16 B load), keeps two tiles in flight in registers,
+// every wave owns a contiguous run of 128 x 64 steps of W, loads the MFMA A fragments straight
+// from HBM (a lane's 8 consecutive k are one 16 B load), keeps a few tiles in flight in registers,
 // takes X fragments from L2 and accumulates with v_mfma_f32_16x16x32_f16 in fp32.  Split-K as in
 // the sparse kernel.
 #include "fls_device.h"
@@ -16,20 +16,28 @@ struct DenseParams {
   OutParams out;
 };
 
-template <int NB, int WAVES>
+// A dense step covers 128 rows x 32*H k, i.e. H MFMA K-steps (H = 1 or 2).  With H = 2 lane l of
+// row block rb reads 32 contiguous bytes of row rb*16 + (l & 15), so the four lanes of a row
+// together read one whole 128 B line; the first 16 B feed the first MFMA, the second 16 B the
+// second one (which 8 k a lane contributes to an MFMA is free as long as the B operand, X, uses
+// the same ones, and it does).  H = 1 halves the registers a step holds, for the wider N.
+
+template <int NB, int WAVES, int NS, int H>
 __global__ __launch_bounds__(WAVES * 64) void dense_kernel(DenseParams p) {
+  constexpr int kDenseK = 32 * H;
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const uint32_t g = blockIdx.x * WAVES + wave, G = gridDim.x * WAVES;
-  const uint32_t T = p.out.T;
-  const uint32_t t0 = (uint32_t)((uint64_t)g * T / G), t1 = (uint32_t)((uint64_t)(g + 1) * T / G);
+  const uint32_t T = p.out.T, KT = p.out.KT;  // steps of 128 x 64 here
   const uint32_t share0 = share_begin(blockIdx.x, T, gridDim.x), share1 = share_begin(blockIdx.x + 1, T, gridDim.x);
+  // The waves of a workgroup take the steps of its share in turn (wave w: share0 + w, + WAVES,
+  // ...), so at any time they read neighbouring 128 B pieces of the same rows: 1 KB runs for the
+  // DRAM instead of eight unrelated ones.
+  const uint32_t t0 = share0 + wave, t1 = share1;
   extern __shared__ __align__(16) unsigned char lds[];
   WgReduceLds<NB>* red = (WgReduceLds<NB>*)lds;
   wg_reduce_init<NB>(red, threadIdx.x, WAVES * 64);
   __syncthreads();  // the only barrier
   if (t0 >= t1) return;
-  const uint32_t KT = p.out.KT;
 
   float4v acc[kRowBlocks][NB];
 #pragma unroll
@@ -37,59 +45,108 @@ __global__ __launch_bounds__(WAVES * 64) void dense_kernel(DenseParams p) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[rb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
 
-  XFrags xf;
-  xf.init(p.X, p.K, p.out.N, p.out.n0, lane);
-  // lane l of row block rb reads row rb*16 + (l & 15), k chunk (l >> 4)
-  const size_t lane_off = (size_t)(lane & 15) * p.K + (lane >> 4) * 8;
+  const uint32_t K = p.K;
+  const uint32_t kgrp = (lane >> 4) * (8 * H);  // first of this lane's 8*H k inside a step
+  const uint32_t lane_off = ((lane & 15) * K + kgrp) * 2u;
+  const uint32_t rb_step = 16u * K * 2u;
+  // X through a descriptor that ends after column N - 1 (padding columns read 0)
+  const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)p.X, 0, (int)(p.out.N * K * 2u), kBufferFlags);
+  const uint32_t x_lane_off = ((p.out.n0 + (lane & 15)) * K + kgrp) * 2u;
+  const uint32_t x_col_step = 16u * K * 2u;
+  // K need not be a multiple of 64: in the last step of a band the lanes whose k lie past K drop out
+  const bool ragged = (K % kDenseK) != 0;
+  const bool lane_past = kgrp + 8 * H > (K % kDenseK);  // this lane's k are past K in a ragged last step
 
-  auto issue = [&](half8(&a)[kRowBlocks], half8(&x)[NB], uint32_t t) {
-    if (t >= t1) return;
-    const uint32_t band = t / KT, kt = t - band * KT;
-    const _Float16* src = p.W + (size_t)band * kTileM * p.K + kt * kTileK + lane_off;
+  // load side (ti) runs NS steps ahead of the consume side (tc)
+  uint32_t ti = t0, kti = t0 % KT, bandi = t0 / KT;
+  uint32_t tc = t0, ktc = kti, bandc = bandi, piece_tiles = 0;
+
+  // No branch encloses the ring's loads: a step past the end of the wave's run gets an empty
+  // buffer descriptor, whose loads return 0 and move no data.  In a ragged last step the lanes
+  // past K read the next row's first bytes (inside the descriptor); they are zeroed before use.
+  auto issue = [&](half8(&a)[kRowBlocks][H], half8(&x)[NB][H]) {
+    const _Float16* base = p.W + ((size_t)bandi * kTileM * K + (size_t)kti * kDenseK);
+    const uint32_t kleft = K - kti * kDenseK;  // k from this step's start to the end of the row
+    const uint32_t span = (127u * K + (kleft < (uint32_t)kDenseK ? kleft : (uint32_t)kDenseK)) * 2u;
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, ti < t1 ? (int)span : 0, kBufferFlags);
 #pragma unroll
     for (int rb = 0; rb < kRowBlocks; ++rb)
-      a[rb] = __builtin_nontemporal_load((const half8*)(src + (size_t)rb * 16 * p.K));
-    xf.template load<NB>(x, kt);
-  };
-
-  uint32_t piece_tiles = 0;
-  HandoverState hs;
-  auto consume = [&](half8(&a)[kRowBlocks], half8(&x)[NB], uint32_t t) {
-    const uint32_t band = t / KT, kt = t - band * KT;
 #pragma unroll
-    for (int rb = 0; rb < kRowBlocks; ++rb)
+      for (int h = 0; h < H; ++h)
+        a[rb][h] = __builtin_bit_cast(
+            half8, __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane_off + rb * rb_step + h * 16, 0, kAuxNonTemporal));
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) acc[rb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[rb], x[nb], acc[rb][nb], 0, 0, 0);
-    ++piece_tiles;
-    if (kt + 1 == KT || t + 1 == t1) {
-      hand_over_piece<NB>(p.out, red, acc, hs, band, piece_tiles, share0, share1, blockIdx.x, lane, false);
-      piece_tiles = 0;
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int h = 0; h < H; ++h)
+        x[nb][h] = __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, x_lane_off + nb * x_col_step + h * 16,
+                                                                                 kti * (kDenseK * 2u), 0));
+    ti += WAVES;
+    kti += WAVES;
+    while (kti >= KT) {
+      kti -= KT;
+      ++bandi;
     }
   };
 
-  half8 aa[kRowBlocks], ab[kRowBlocks], xa[NB], xb[NB];
-  issue(aa, xa, t0);
-  issue(ab, xb, t0 + 1);
-  for (uint32_t t = t0; t < t1; t += 2) {
-    consume(aa, xa, t);
-    issue(aa, xa, t + 2);
-    if (t + 1 >= t1) break;
-    consume(ab, xb, t + 1);
-    issue(ab, xb, t + 3);
+  HandoverState hs;
+  half8 a[NS][kRowBlocks][H], x[NS][NB][H];
+#pragma unroll
+  for (int i = 0; i < NS; ++i) issue(a[i], x[i]);
+
+  auto step = [&](half8(&sa)[kRowBlocks][H], half8(&sx)[NB][H]) {
+    if (ragged && ktc + 1 == KT && lane_past) {
+      // k past the end of the row: take them out of the product (X side is enough)
+      const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int h = 0; h < H; ++h) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) sx[nb][h] = z;
+#pragma unroll
+        for (int rb = 0; rb < kRowBlocks; ++rb) sa[rb][h] = z;
+      }
+    }
+#pragma unroll
+    for (int rb = 0; rb < kRowBlocks; ++rb)
+#pragma unroll
+      for (int h = 0; h < H; ++h)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+          acc[rb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(sa[rb][h], sx[nb][h], acc[rb][nb], 0, 0, 0);
+    issue(sa, sx);
+    ++piece_tiles;
+    tc += WAVES;
+    ktc += WAVES;
+    if (ktc >= KT || tc >= t1) {  // the wave's next step is in another band, or there is none
+      hand_over_piece<NB>(p.out, red, acc, hs, bandc, piece_tiles, share0, share1, blockIdx.x, lane, false);
+      piece_tiles = 0;
+      while (ktc >= KT) {
+        ktc -= KT;
+        ++bandc;
+      }
+    }
+  };
+
+  while (tc + (NS - 1) * WAVES < t1) {
+#pragma unroll
+    for (int i = 0; i < NS; ++i) step(a[i], x[i]);
   }
+#pragma unroll
+  for (int i = 0; i < NS - 1; ++i)
+    if (tc < t1) step(a[i], x[i]);
   hand_over_finish<NB>(p.out, acc, hs, blockIdx.x, gridDim.x, lane);
 }
 
-template <int NB, int WAVES>
+template <int NB, int WAVES, int NS, int H>
 static hipError_t launch_dense_variant(const DenseParams& p, int grid, hipStream_t stream) {
   static bool attr_done = false;
   const int lds_bytes = (int)sizeof(WgReduceLds<NB>);
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)dense_kernel<NB, WAVES>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    hipError_t e = hipFuncSetAttribute((const void*)dense_kernel<NB, WAVES, NS, H>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL((dense_kernel<NB, WAVES>), dim3(grid), dim3(WAVES * 64), lds_bytes, stream, p);
+  hipLaunchKernelGGL((dense_kernel<NB, WAVES, NS, H>), dim3(grid), dim3(WAVES * 64), lds_bytes, stream, p);
   return hipGetLastError();
 }
 
@@ -98,22 +155,22 @@ hipError_t launch_dense(const DenseLaunch& a, hipStream_t stream) {
   p.W = a.W;
   p.X = a.X;
   p.K = a.K;
-  p.out.T = (a.M / kTileM) * (a.K / kTileK);
   p.out.C = a.C;
   p.out.parts = a.parts;
   p.out.flags = a.flags;
   p.out.M = a.M;
   p.out.N = a.N;
-  p.out.KT = a.K / kTileK;
   const int grid = pick_grid(a.M / kTileM, a.num_cus);
-  for (uint32_t n0 = 0; n0 < a.N; n0 += 64) {
+  for (uint32_t n0 = 0; n0 < a.N; n0 += kGroupCols) {
     p.out.n0 = n0;
-    p.out.epoch = a.epoch0 + n0 / 64;
-    const uint32_t ncols = a.N - n0 < 64 ? a.N - n0 : 64;
+    p.out.epoch = a.epoch0 + n0 / kGroupCols;
+    const uint32_t ncols = a.N - n0 < kGroupCols ? a.N - n0 : kGroupCols;
     hipError_t e;
-    if (ncols <= 16) e = launch_dense_variant<1, 8>(p, grid, stream);
-    else if (ncols <= 32) e = launch_dense_variant<2, 8>(p, grid, stream);
-    else e = launch_dense_variant<4, 8>(p, grid, stream);
+    const uint32_t h = ncols <= 16 ? 2 : 1;
+    p.out.KT = (a.K + 32 * h - 1) / (32 * h);
+    p.out.T = (a.M / kTileM) * p.out.KT;
+    if (ncols <= 16) e = launch_dense_variant<1, 8, 2, 2>(p, grid, stream);
+    else e = launch_dense_variant<2, 8, 2, 1>(p, grid, stream);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;

@@ -222,12 +222,13 @@ __device__ __forceinline__ void owner_finish(const OutParams& o, float4v (&acc)[
       }
     }
   }
-  // The loads of up to kBatch slots are all issued before the first is used: each is a trip to
-  // memory, and this runs when the kernel is about to end, with nothing left to hide it behind.
-  constexpr int kBatch = NB == 1 ? 4 : (NB == 2 ? 2 : 1);
+  // As many loads as the registers allow are issued before the first is used: each is a trip
+  // to memory, and this runs when the kernel is about to end, with nothing left to hide it behind.
+  constexpr int kBatch = NB == 1 ? 4 : (NB == 2 ? 2 : 1);  // slots in flight
+  constexpr int kBlocks = NB == 4 ? 2 : NB;                 // column blocks of a slot in flight
   uint32_t q = wg + 1;
   while (q < P && share_begin(q, o.T, P) < band_hi) {
-    u32x4 v[kBatch][NB][kRowBlocks];
+    __amdgpu_buffer_rsrc_t src[kBatch];
 #pragma unroll
     for (int j = 0; j < kBatch; ++j) {
       // next workgroup with tiles of the band; past the last one the descriptor is empty and reads 0
@@ -236,22 +237,28 @@ __device__ __forceinline__ void owner_finish(const OutParams& o, float4v (&acc)[
         found = share_begin(q + 1, o.T, P) != share_begin(q, o.T, P);
         if (!found) ++q;
       }
-      const __amdgpu_buffer_rsrc_t src =
-          __builtin_amdgcn_make_buffer_rsrc((void*)(o.parts + (size_t)(found ? q : 0u) * (NB * kAccPerBlock)), 0,
-                                            found ? NB * kAccPerBlock * 4 : 0, kBufferFlags);
+      src[j] = __builtin_amdgcn_make_buffer_rsrc((void*)(o.parts + (size_t)(found ? q : 0u) * (NB * kAccPerBlock)), 0,
+                                                 found ? NB * kAccPerBlock * 4 : 0, kBufferFlags);
       if (found) ++q;
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-        for (int rb = 0; rb < kRowBlocks; ++rb)
-          v[j][nb][rb] = __builtin_amdgcn_raw_buffer_load_b128(src, ((nb * kRowBlocks + rb) * 64 + lane) * 16, 0, kAuxCoherent);
     }
 #pragma unroll
-    for (int j = 0; j < kBatch; ++j)
+    for (int nb0 = 0; nb0 < NB; nb0 += kBlocks) {
+      u32x4 v[kBatch][kBlocks][kRowBlocks];
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
+      for (int j = 0; j < kBatch; ++j)
 #pragma unroll
-        for (int rb = 0; rb < kRowBlocks; ++rb) acc[rb][nb] += __builtin_bit_cast(float4v, v[j][nb][rb]);
+        for (int nb = 0; nb < kBlocks; ++nb)
+#pragma unroll
+          for (int rb = 0; rb < kRowBlocks; ++rb)
+            v[j][nb][rb] = __builtin_amdgcn_raw_buffer_load_b128(src[j], (((nb0 + nb) * kRowBlocks + rb) * 64 + lane) * 16, 0,
+                                                                 kAuxCoherent);
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j)
+#pragma unroll
+        for (int nb = 0; nb < kBlocks; ++nb)
+#pragma unroll
+          for (int rb = 0; rb < kRowBlocks; ++rb) acc[rb][nb0 + nb] += __builtin_bit_cast(float4v, v[j][nb][rb]);
+    }
   }
   store_band<NB>(o, acc, band, lane);
 }

@@ -36,12 +36,15 @@ struct CompressLaunch {
   uint32_t policy;
 };
 
-// Columns are processed in groups of up to 64; a group of c columns runs as 1, 2 or 4 MFMA column
-// blocks of 16.
+// Columns are processed in groups of up to kGroupCols, one launch per group (each streams W
+// again); a group of c columns runs as 1 or 2 MFMA column blocks of 16.  Wider groups (4 blocks,
+// 128 accumulator registers per wave) exist in the kernels but spill today, so they are not used.
+constexpr uint32_t kGroupCols = 32;
+inline uint32_t column_groups(uint32_t N) { return (N + kGroupCols - 1) / kGroupCols; }
 inline uint32_t group_blocks(uint32_t ncols) { return ncols <= 16 ? 1u : (ncols <= 32 ? 2u : 4u); }
 constexpr uint32_t kMaxWorkgroups = 512;    // must equal fls::kMaxGrid of the device code
 // fp32 values of the split-K partial slots: [workgroup][column blocks][128 x 16]
-inline size_t parts_floats(uint32_t N) { return (size_t)kMaxWorkgroups * group_blocks(N < 64 ? N : 64) * 2048; }
+inline size_t parts_floats(uint32_t N) { return (size_t)kMaxWorkgroups * group_blocks(N < kGroupCols ? N : kGroupCols) * 2048; }
 
 // Number of workgroups for a matrix of `bands` row bands on `cus` compute units (one workgroup
 // per CU at most).  A count of the form bands * k gives every band to exactly k workgroups: with

@@ -154,22 +154,27 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   // them: the LDS runs a wave's operations in order, so the zeros cannot overtake the reads, and
   // the MFMAs then wait for the reads only.
   auto compute = [&](const half8(&x)[NB]) {
-    half8 a[kRowBlocks];
+    // fragments of H row blocks at a time (all eight when the accumulators leave the registers for it)
+    constexpr int H = NB == 1 ? 8 : (NB == 2 ? 4 : 2);
 #pragma unroll
-    for (int rb = 0; rb < kRowBlocks; ++rb) {
-      if (FLS_ABLATE & 16) a[rb] = x[0];
-      else a[rb] = *(const half8*)(frag + rb * 256);
-    }
-    if (!(FLS_ABLATE & 8)) {
+    for (int h = 0; h < kRowBlocks; h += H) {
+      half8 a[H];
 #pragma unroll
-      for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
-    }
+      for (int j = 0; j < H; ++j) {
+        if (FLS_ABLATE & 16) a[j] = x[0];
+        else a[j] = *(const half8*)(frag + (h + j) * 256);
+      }
+      if (h + H == kRowBlocks && !(FLS_ABLATE & 8)) {
 #pragma unroll
-    for (int rb = 0; rb < kRowBlocks; ++rb) {
+        for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
+      }
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        if (FLS_ABLATE & 2) acc[rb][nb][0] += (float)a[rb][0] * (float)x[nb][0];
-        else acc[rb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[rb], x[nb], acc[rb][nb], 0, 0, 0);
+      for (int j = 0; j < H; ++j) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          if (FLS_ABLATE & 2) acc[h + j][nb][0] += (float)a[j][0] * (float)x[nb][0];
+          else acc[h + j][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[j], x[nb], acc[h + j][nb], 0, 0, 0);
+        }
       }
     }
   };
@@ -211,6 +216,13 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   for (int i = 0; i < NS; ++i) issue(s[i], x[i], sb[i], se[i]);
 
   auto step = [&](u32x4(&ss)[R], half8(&sx)[NB], uint32_t& b, uint32_t& e) {
+#ifdef FLS_PRIO_FLIP
+    // Two waves share a SIMD and the older one wins every issue slot when both are ready, so it
+    // would finish its run microseconds ahead of the younger.  Alternating the priority tile by
+    // tile gives both the same share of the SIMD.
+    if (((tc ^ (wave >> 2)) & 1u) != 0) __builtin_amdgcn_s_setprio(1);
+    else __builtin_amdgcn_s_setprio(0);
+#endif
     extract(ss, b, e);
     half8 xc[NB];
 #pragma unroll
@@ -247,7 +259,6 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 #ifndef FLS_WAVES
 #define FLS_WAVES 8
 #endif
-
 template <int NB, int WAVES, int R>
 static hipError_t launch_variant(const SpmmParams& p, int grid, hipStream_t stream) {
   constexpr int NS = NB == 1 ? FLS_NSTAGE : 2;  // wider accumulators leave room for a shallower ring
@@ -293,14 +304,13 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
   if (a.max_tile_words <= 2 * 256) R = 2;
   else if (a.max_tile_words <= 4 * 256) R = 4;
   else if (a.max_tile_words <= 6 * 256) R = 6;
-  for (uint32_t n0 = 0; n0 < a.N; n0 += 64) {
+  for (uint32_t n0 = 0; n0 < a.N; n0 += kGroupCols) {
     p.out.n0 = n0;
-    p.out.epoch = a.epoch0 + n0 / 64;
-    const uint32_t ncols = a.N - n0 < 64 ? a.N - n0 : 64;
+    p.out.epoch = a.epoch0 + n0 / kGroupCols;
+    const uint32_t ncols = a.N - n0 < kGroupCols ? a.N - n0 : kGroupCols;
     hipError_t e;
     if (ncols <= 16) e = launch_r<1, FLS_WAVES>(R, p, grid, stream);
-    else if (ncols <= 32) e = launch_r<2, FLS_WAVES>(R, p, grid, stream);
-    else e = launch_r<4, FLS_WAVES>(R, p, grid, stream);
+    else e = launch_r<2, FLS_WAVES>(R, p, grid, stream);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
