@@ -2,10 +2,10 @@
 // reformatting step, Sec. 5; format Sec. 4.3.1-4.3.2; tile walk of Alg. 3).
 //
 // Three kernels, all integer work on fp16 bit patterns (no value passes through a float op):
-//   count : one wave per tile counts the non-zero bit patterns -> padded run length, written
-//           in place into the TileOffsets section; nnz and the longest run go to the header
-//   scan  : one workgroup turns the run lengths into exclusive prefix sums, fills the guard
-//           entries and the rest of the header
+//   count : one wave per tile counts the non-zero bit patterns and leaves the count in the
+//           tile's TileOffsets entry
+//   scan  : one workgroup turns the counts into padded run lengths and their exclusive prefix
+//           sums, fills the guard entries, and writes the header (nnz, longest run included)
 //   emit  : one wave per tile walks the tile in location order; per step every lane holds the 8
 //           halves of one (row, K-chunk) cell, a wave prefix sum of the per-lane counts gives each
 //           lane its slot in the run (ordered compaction)
@@ -66,24 +66,36 @@ __global__ __launch_bounds__(256) void compress_count_kernel(CompressParams p) {
     cnt += __popc(nonzero_mask(v));
   }
   cnt = wave_sum(cnt);
-  if (lane == 0) {
-    const uint32_t words = (cnt + kPad - 1) / kPad * kPad;
-    offs_of(p)[t] = words;
-    atomicAdd((unsigned long long*)(p.out + 48), (unsigned long long)cnt);  // header.nnz
-    atomicMax((uint32_t*)(p.out + 24), words);                              // header.max_tile_words
-  }
+  if (lane == 0) offs_of(p)[t] = cnt;
 }
+
+__device__ __forceinline__ uint32_t padded(uint32_t cnt) { return (cnt + kPad - 1) / kPad * kPad; }
 
 // single workgroup of 1024 threads
 __global__ __launch_bounds__(1024) void compress_scan_kernel(CompressParams p) {
   __shared__ unsigned long long part[1024];
+  __shared__ unsigned long long nnz_total;
+  __shared__ uint32_t longest;
   uint32_t* offs = offs_of(p);
   const uint32_t tid = threadIdx.x;
   const uint32_t per = (p.T + 1023) / 1024;
   const uint32_t a = tid * per < p.T ? tid * per : p.T, b = (tid + 1) * per < p.T ? (tid + 1) * per : p.T;
-  unsigned long long s = 0;
-  for (uint32_t i = a; i < b; ++i) s += offs[i];
+  if (tid == 0) {
+    nnz_total = 0;
+    longest = 0;
+  }
+  __syncthreads();
+  unsigned long long s = 0, nnz = 0;
+  uint32_t mx = 0;
+  for (uint32_t i = a; i < b; ++i) {
+    const uint32_t cnt = offs[i], w = padded(cnt);
+    nnz += cnt;
+    s += w;
+    mx = w > mx ? w : mx;
+  }
   part[tid] = s;
+  atomicAdd(&nnz_total, nnz);  // 1024 LDS atomics in all
+  atomicMax(&longest, mx);
   __syncthreads();
   // Hillis-Steele inclusive scan over the 1024 partial sums
   for (uint32_t d = 1; d < 1024; d <<= 1) {
@@ -95,7 +107,7 @@ __global__ __launch_bounds__(1024) void compress_scan_kernel(CompressParams p) {
   unsigned long long run = tid ? part[tid - 1] : 0;
   const unsigned long long total = part[1023];
   for (uint32_t i = a; i < b; ++i) {
-    const uint32_t w = offs[i];
+    const uint32_t w = padded(offs[i]);
     offs[i] = (uint32_t)run;
     run += w;
   }
@@ -108,11 +120,12 @@ __global__ __launch_bounds__(1024) void compress_scan_kernel(CompressParams p) {
     h[3] = kTileK;
     h[4] = kPad;
     h[5] = p.policy;
-    // h[6] = max_tile_words (count kernel), h[7] = 0
+    h[6] = longest;
+    h[7] = 0u;
     unsigned long long* q = (unsigned long long*)(p.out + 32);
     q[0] = p.M;
     q[1] = p.K;
-    // q[2] = nnz (count kernel)
+    q[2] = nnz_total;
     q[3] = total;
   }
 }

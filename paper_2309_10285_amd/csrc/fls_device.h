@@ -314,27 +314,51 @@ __device__ __forceinline__ void hand_over_finish(const OutParams& o, float4v (&a
   if (st.own) owner_finish<NB>(o, acc, st.own_band, wg, P, lane);
 }
 
-// B operand fragments (X) of one K tile, straight from global memory (they stay in L2): lane l
-// supplies column (l & 15) and the 8 consecutive k of chunk (l >> 4); X is column-major so they
-// are one 16 B load.  The loads go through a buffer descriptor that ends after column N - 1, so
-// the columns that pad N up to a multiple of 16 read as zero without a branch or a select after
-// the load (either would make the compiler wait for the load on the spot).
+// B operand fragments (X) of one K tile.  An MFMA wants lane l to hold column (l & 15) and the 8
+// consecutive k of chunk (l >> 4), but loading X that way makes the four neighbouring lanes of
+// every quad read four different cache lines (X is column-major).  So the load assigns lane j
+// column (j >> 2) and chunk (j & 3) - a quad reads 64 contiguous bytes - and the fragment is put
+// into MFMA order through a 1 KB LDS block per 16 columns: written as loaded, read back
+// transposed.  The slot permutation keeps both the 16 B writes and the 16 B reads free of bank
+// conflicts (any 16 neighbouring lanes touch 16 different 16 B slots modulo 256 B).
+//
+// The loads go through a buffer descriptor that ends after column N - 1, so the columns that pad
+// N up to a multiple of 16 read as zero without a branch or a select after the load (either
+// would make the compiler wait for the load on the spot).
 struct XFrags {
   __amdgpu_buffer_rsrc_t rsrc;
-  uint32_t lane_off;  // byte offset of this lane's column and k chunk
+  uint32_t lane_off;  // byte offset of the column and k chunk this lane loads
   uint32_t col_step;  // bytes between column blocks
+  uint32_t wslot;     // byte offset in a column block's LDS stage where this lane's load goes
+  uint32_t rslot;     // ... and where this lane's MFMA fragment comes from
 
+  // 16 B slot of (column c, chunk g) of a 16-column block
+  static __device__ __forceinline__ uint32_t slot(uint32_t c, uint32_t g) {
+    return 16u * (c >> 2) + 4u * (c & 3u) + (g ^ (c >> 2));
+  }
   __device__ __forceinline__ void init(const _Float16* X, uint32_t K, uint32_t N, uint32_t n0, int lane) {
     rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)X, 0, (int)(N * K * 2u), kBufferFlags);
-    lane_off = ((n0 + (lane & 15)) * K + (lane >> 4) * 8) * 2u;
+    const uint32_t c = (uint32_t)lane >> 2, g = (uint32_t)lane & 3u;
+    lane_off = ((n0 + c) * K + g * 8u) * 2u;
     col_step = 16u * K * 2u;
+    wslot = slot(c, g) * 16u;
+    rslot = slot((uint32_t)lane & 15u, (uint32_t)lane >> 4) * 16u;
   }
   template <int NB>
-  __device__ __forceinline__ void load(half8 (&x)[NB], uint32_t kt) const {
+  __device__ __forceinline__ void load(u32x4 (&x)[NB], uint32_t kt) const {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
-      x[nb] = __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane_off + nb * col_step,
-                                                                              kt * (kTileK * 2u), 0));
+      x[nb] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane_off + nb * col_step, kt * (kTileK * 2u), 0);
+  }
+  // loaded registers -> the wave's LDS stage (NB KB)
+  template <int NB>
+  __device__ __forceinline__ void stage(unsigned char* xs, const u32x4 (&x)[NB]) const {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) *(u32x4*)(xs + nb * 1024 + wslot) = x[nb];
+  }
+  // MFMA B fragment of column block nb
+  __device__ __forceinline__ half8 frag(const unsigned char* xs, int nb) const {
+    return *(const half8*)(xs + nb * 1024 + rslot);
   }
 };
 

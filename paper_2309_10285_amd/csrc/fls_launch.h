@@ -36,15 +36,20 @@ struct CompressLaunch {
   uint32_t policy;
 };
 
-// Columns are processed in groups of up to kGroupCols, one launch per group (each streams W
-// again); a group of c columns runs as 1 or 2 MFMA column blocks of 16.  Wider groups (4 blocks,
-// 128 accumulator registers per wave) exist in the kernels but spill today, so they are not used.
+// Columns are processed in groups, one launch per group (each streams W again); a group runs as
+// 1, 2 or 4 MFMA column blocks of 16.  The dense baseline takes groups of up to kGroupCols columns.
+// The sparse kernel takes up to kSpmmGroupCols: its four-block variant runs four waves per
+// workgroup instead of eight, so that a wave may use the whole register file of its SIMD
+// (128 accumulator registers and a deep load ring do not fit in half of it).
 constexpr uint32_t kGroupCols = 32;
-inline uint32_t column_groups(uint32_t N) { return (N + kGroupCols - 1) / kGroupCols; }
+constexpr uint32_t kSpmmGroupCols = 64;
+inline uint32_t column_groups(uint32_t N) { return (N + kGroupCols - 1) / kGroupCols; }  // upper bound on launches per call
 inline uint32_t group_blocks(uint32_t ncols) { return ncols <= 16 ? 1u : (ncols <= 32 ? 2u : 4u); }
 constexpr uint32_t kMaxWorkgroups = 512;    // must equal fls::kMaxGrid of the device code
 // fp32 values of the split-K partial slots: [workgroup][column blocks][128 x 16]
-inline size_t parts_floats(uint32_t N) { return (size_t)kMaxWorkgroups * group_blocks(N < kGroupCols ? N : kGroupCols) * 2048; }
+inline size_t parts_floats(uint32_t N) {
+  return (size_t)kMaxWorkgroups * group_blocks(N < kSpmmGroupCols ? N : kSpmmGroupCols) * 2048;
+}
 
 // Number of workgroups for a matrix of `bands` row bands on `cus` compute units (one workgroup
 // per CU at most).  A count of the form bands * k gives every band to exactly k workgroups: with

@@ -25,7 +25,8 @@
 
 namespace fls {
 
-constexpr int kWaveLds = kTileBytes + 16;  // + the slot that padding words land in
+// LDS of one wave: its tile, the 16 B slot that padding words land in, the X stage (1 KB per column block)
+constexpr int wave_lds(int NB) { return kTileBytes + 16 + NB * 1024; }
 
 struct SpmmParams {
   const uint32_t* offs;   // TileOffsets
@@ -81,6 +82,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   const uint32_t T = p.out.T, KT = p.out.KT;
   const uint32_t t0 = (uint32_t)((uint64_t)g * T / G), t1 = (uint32_t)((uint64_t)(g + 1) * T / G);
   const uint32_t share0 = share_begin(blockIdx.x, T, gridDim.x), share1 = share_begin(blockIdx.x + 1, T, gridDim.x);
+  constexpr int kWaveLds = wave_lds(NB);
   WgReduceLds<NB>* red = (WgReduceLds<NB>*)(lds + WAVES * kWaveLds);
   wg_reduce_init<NB>(red, threadIdx.x, WAVES * 64);
   __syncthreads();  // the only barrier: from here on the waves run independently
@@ -88,6 +90,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   if (t0 >= t1) return;
 
   unsigned char* tile = lds + wave * kWaveLds;
+  unsigned char* xs = tile + kTileBytes + 16;
   const u32x4 zero4 = {0u, 0u, 0u, 0u};
 #pragma unroll
   for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
@@ -115,7 +118,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   // back to "wait for everything" and the ring would be lost), so a lane past the end of the
   // run, or a tile past the end of the wave's tiles, is turned away by the bounds check of the
   // buffer descriptor instead: it returns 0 and moves no data.
-  auto issue = [&](u32x4(&s)[R], half8(&x)[NB], uint32_t& begin, uint32_t& end) {
+  auto issue = [&](u32x4(&s)[R], u32x4(&x)[NB], uint32_t& begin, uint32_t& end) {
     win.get(ti, begin, end);
     uint32_t n = end - begin;
     if (n > R * 256u) n = R * 256u;
@@ -153,9 +156,12 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   // smem2tc + rst_smem.  All fragment reads are issued first and the re-zeroing right behind
   // them: the LDS runs a wave's operations in order, so the zeros cannot overtake the reads, and
   // the MFMAs then wait for the reads only.
-  auto compute = [&](const half8(&x)[NB]) {
+  auto compute = [&]() {
+    half8 x[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) x[nb] = xf.frag(xs, nb);
     // fragments of H row blocks at a time (all eight when the accumulators leave the registers for it)
-    constexpr int H = NB == 1 ? 8 : (NB == 2 ? 4 : 2);
+    constexpr int H = (NB == 1 || WAVES <= 4) ? 8 : (NB == 2 ? 4 : 2);
 #pragma unroll
     for (int h = 0; h < kRowBlocks; h += H) {
       half8 a[H];
@@ -210,12 +216,12 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   // condition - which lets the compiler wait for exactly the stage it needs
   // (s_waitcnt vmcnt(n), n = loads issued since).
   u32x4 s[NS][R];
-  half8 x[NS][NB];
+  u32x4 x[NS][NB];
   uint32_t sb[NS], se[NS];  // word range of the tile each stage holds
 #pragma unroll
   for (int i = 0; i < NS; ++i) issue(s[i], x[i], sb[i], se[i]);
 
-  auto step = [&](u32x4(&ss)[R], half8(&sx)[NB], uint32_t& b, uint32_t& e) {
+  auto step = [&](u32x4(&ss)[R], u32x4(&sx)[NB], uint32_t& b, uint32_t& e) {
 #ifdef FLS_PRIO_FLIP
     // Two waves share a SIMD and the older one wins every issue slot when both are ready, so it
     // would finish its run microseconds ahead of the younger.  Alternating the priority tile by
@@ -224,11 +230,9 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     else __builtin_amdgcn_s_setprio(0);
 #endif
     extract(ss, b, e);
-    half8 xc[NB];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) xc[nb] = sx[nb];
+    xf.template stage<NB>(xs, sx);
     issue(ss, sx, b, e);
-    compute(xc);
+    compute();
     ++piece_tiles;
     ++tc;
     if (++ktc == KT || tc == t1) {
@@ -256,14 +260,26 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 #ifndef FLS_NSTAGE
 #define FLS_NSTAGE 3
 #endif
-#ifndef FLS_WAVES
-#define FLS_WAVES 8
+
+// Tiles in flight per wave.  What has to be kept in flight is bytes, not tiles: about 10 KB per
+// wave (80 KB per CU) covers the latency of HBM, so sparser matrices (fewer rounds R of 256 words
+// per tile) get a deeper ring, as far as the registers allow: a stage costs 4 R + 4 NB registers,
+// the accumulators 32 NB, and a wave has 256 registers with eight waves per workgroup, 512 with four.
+#ifndef FLS_WIDE_WAVES
+#define FLS_WIDE_WAVES 0
 #endif
+constexpr int ring_depth(int NB, int WAVES, int R) {
+  if (NB == 4 && WAVES == 8) return R <= 2 ? 3 : 2;
+  if (WAVES <= 4) return R <= 2 ? 8 : (R <= 4 ? 6 : (R <= 6 ? 4 : 3));
+  if (NB == 1) return FLS_NSTAGE;
+  return R <= 2 ? 4 : 2;
+}
+
 template <int NB, int WAVES, int R>
 static hipError_t launch_variant(const SpmmParams& p, int grid, hipStream_t stream) {
-  constexpr int NS = NB == 1 ? FLS_NSTAGE : 2;  // wider accumulators leave room for a shallower ring
+  constexpr int NS = ring_depth(NB, WAVES, R);
   static bool attr_done = false;
-  const int lds_bytes = WAVES * kWaveLds + (int)sizeof(WgReduceLds<NB>);
+  const int lds_bytes = WAVES * wave_lds(NB) + (int)sizeof(WgReduceLds<NB>);
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)spmm_kernel<NB, WAVES, R, NS>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        lds_bytes);
@@ -304,13 +320,22 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
   if (a.max_tile_words <= 2 * 256) R = 2;
   else if (a.max_tile_words <= 4 * 256) R = 4;
   else if (a.max_tile_words <= 6 * 256) R = 6;
-  for (uint32_t n0 = 0; n0 < a.N; n0 += kGroupCols) {
+  uint32_t launches = 0;
+  for (uint32_t n0 = 0; n0 < a.N;) {
     p.out.n0 = n0;
-    p.out.epoch = a.epoch0 + n0 / kGroupCols;
-    const uint32_t ncols = a.N - n0 < kGroupCols ? a.N - n0 : kGroupCols;
+    p.out.epoch = a.epoch0 + launches++;
+    const uint32_t left = a.N - n0;
     hipError_t e;
-    if (ncols <= 16) e = launch_r<1, FLS_WAVES>(R, p, grid, stream);
-    else e = launch_r<2, FLS_WAVES>(R, p, grid, stream);
+    if (left <= 16) {
+      e = launch_r<1, 8>(R, p, grid, stream);
+      n0 += 16;
+    } else if (left <= 32 || FLS_WIDE_WAVES == 0) {
+      e = launch_r<2, 8>(R, p, grid, stream);
+      n0 += 32;
+    } else {
+      e = launch_r<4, FLS_WIDE_WAVES ? FLS_WIDE_WAVES : 4>(R, p, grid, stream);
+      n0 += kSpmmGroupCols;
+    }
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
