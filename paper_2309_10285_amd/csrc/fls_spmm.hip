@@ -110,19 +110,23 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   win.load(t0);
   const unsigned char* frag = tile + ((lane >> 4) * kTileM + (lane & 15)) * 16;
 
-  // Load side: tile ti is the next to be requested; consume side: tile tc is the next to be used.
-  uint32_t ti = t0, kti = t0 % KT;
-  uint32_t tc = t0, ktc = kti, bandc = t0 / KT, piece_tiles = 0;
+  // A wave's run [t0, t1) is walked piece by piece, a piece being its tiles of one row band
+  // [tc, pend).  Load side: tile ti is the next to be requested; consume side: tile tc is the
+  // next to be used.
+  uint32_t tc = t0, ktc = t0 % KT, bandc = t0 / KT;
+  uint32_t ti = tc, kti = ktc, pend = tc;
 
   // gmem2reg.  No branch may enclose the ring's loads (the compiler's vmcnt bookkeeping would fall
   // back to "wait for everything" and the ring would be lost), so a lane past the end of the
   // run, or a tile past the end of the wave's tiles, is turned away by the bounds check of the
-  // buffer descriptor instead: it returns 0 and moves no data.
+  // buffer descriptor instead: it returns 0 and moves no data.  Nothing is requested past the
+  // end of the piece either: the ring runs empty there, so that the hand-over that follows has
+  // the registers to itself (no value of the ring is live across it).
   auto issue = [&](u32x4(&s)[R], u32x4(&x)[NB], uint32_t& begin, uint32_t& end) {
     win.get(ti, begin, end);
     uint32_t n = end - begin;
     if (n > R * 256u) n = R * 256u;
-    if (ti >= t1) n = 0;
+    if (ti >= pend) n = 0;
     const __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void*)(p.words + begin), 0, (int)(n * 4u), kBufferFlags);
 #pragma unroll
@@ -185,9 +189,9 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     }
   };
 
-  // Hand-over of the piece that just ended in `band`.
+  // Hand-over of the piece of `tiles` tiles that just ended in `band`.
   HandoverState hs;
-  auto hand_over = [&](uint32_t band) {
+  auto hand_over = [&](uint32_t band, uint32_t tiles) {
     if (tc == t1) FLS_STAMP(p.out.flags, 256 + blockIdx.x, wave);  // debug builds: end of every wave's run
     if (FLS_ABLATE & 1) {
       float sum = 0.f;  // keeps every accumulator alive
@@ -199,9 +203,8 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     } else if (FLS_ABLATE & 128) {
       store_band<NB>(p.out, acc, band, lane);
     } else {
-      hand_over_piece<NB>(p.out, red, acc, hs, band, piece_tiles, share0, share1, blockIdx.x, lane, (FLS_ABLATE & 64) != 0);
+      hand_over_piece<NB>(p.out, red, acc, hs, band, tiles, share0, share1, blockIdx.x, lane, (FLS_ABLATE & 64) != 0);
     }
-    piece_tiles = 0;
     if (FLS_ABLATE & (1 | 128)) {
 #pragma unroll
       for (int rb = 0; rb < kRowBlocks; ++rb)
@@ -218,8 +221,6 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   u32x4 s[NS][R];
   u32x4 x[NS][NB];
   uint32_t sb[NS], se[NS];  // word range of the tile each stage holds
-#pragma unroll
-  for (int i = 0; i < NS; ++i) issue(s[i], x[i], sb[i], se[i]);
 
   auto step = [&](u32x4(&ss)[R], u32x4(&sx)[NB], uint32_t& b, uint32_t& e) {
 #ifdef FLS_PRIO_FLIP
@@ -233,24 +234,30 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     xf.template stage<NB>(xs, sx);
     issue(ss, sx, b, e);
     compute();
-    ++piece_tiles;
     ++tc;
-    if (++ktc == KT || tc == t1) {
-      hand_over(bandc);
-      if (ktc == KT) {
-        ktc = 0;
-        ++bandc;
-      }
-    }
   };
 
-  while (tc + NS <= t1) {
+  while (tc < t1) {
+    const uint32_t piece0 = tc;
+    pend = tc + (KT - ktc) < t1 ? tc + (KT - ktc) : t1;
+    ti = tc;
+    kti = ktc;
 #pragma unroll
-    for (int i = 0; i < NS; ++i) step(s[i], x[i], sb[i], se[i]);
+    for (int i = 0; i < NS; ++i) issue(s[i], x[i], sb[i], se[i]);
+    while (tc + NS <= pend) {
+#pragma unroll
+      for (int i = 0; i < NS; ++i) step(s[i], x[i], sb[i], se[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < NS - 1; ++i)
+      if (tc < pend) step(s[i], x[i], sb[i], se[i]);
+    hand_over(bandc, pend - piece0);
+    ktc += pend - piece0;
+    if (ktc == KT) {
+      ktc = 0;
+      ++bandc;
+    }
   }
-#pragma unroll
-  for (int i = 0; i < NS - 1; ++i)
-    if (tc < t1) step(s[i], x[i], sb[i], se[i]);
   hand_over_finish<NB>(p.out, acc, hs, blockIdx.x, gridDim.x, lane);
   if (wave == 0) FLS_STAMP(p.out.flags, blockIdx.x, 2);
 }
