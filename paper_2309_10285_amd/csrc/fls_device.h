@@ -83,11 +83,14 @@ __device__ __forceinline__ void store_band(const OutParams& o, const float4v (&a
   }
 }
 
-// LDS area of the in-workgroup step: two band slots and their control words.
-// A slot keeps a band's running sum as [column block][row block][lane] float4.
+// LDS area of the in-workgroup step: band slots and their control words.  A slot keeps a band's
+// running sum as [column block][row block][lane] float4.  Consecutive bands of a workgroup's
+// share alternate between two slots, so that waves already in the next band need not wait for
+// the previous one to be collected; with four column blocks a slot is 32 KB and there is one.
 template <int NB>
 struct WgReduceLds {
-  float4v slot[2][NB * kRowBlocks * 64];
+  static constexpr uint32_t kSlots = NB <= 2 ? 2 : 1;
+  float4v slot[kSlots][NB * kRowBlocks * 64];
   uint32_t cnt[2];   // tiles added to the slot so far
   uint32_t gen[2];   // how many bands the slot has served
   uint32_t lock[2];  // 1 while a wave is adding to the slot
@@ -95,7 +98,7 @@ struct WgReduceLds {
 
 template <int NB>
 __device__ __forceinline__ void wg_reduce_init(WgReduceLds<NB>* red, int tid, int nthreads) {
-  for (int i = tid; i < 2 * NB * kRowBlocks * 64; i += nthreads) (&red->slot[0][0])[i] = float4v{0.f, 0.f, 0.f, 0.f};
+  for (int i = tid; i < (int)WgReduceLds<NB>::kSlots * NB * kRowBlocks * 64; i += nthreads) (&red->slot[0][0])[i] = float4v{0.f, 0.f, 0.f, 0.f};
   if (tid < 2) {
     red->cnt[tid] = 0;
     red->gen[tid] = 0;
@@ -112,8 +115,8 @@ __device__ __forceinline__ void wg_reduce_init(WgReduceLds<NB>* red, int tid, in
 template <int NB>
 __device__ __forceinline__ bool wg_reduce_add(WgReduceLds<NB>* red, const float4v (&acc)[kRowBlocks][NB], uint32_t seq,
                                               uint32_t tiles, uint32_t expected, int lane) {
-  const uint32_t s = seq & 1u, turn = seq >> 1;
-  // the slot may still serve band seq - 2 (only when a workgroup's share spans more than two bands)
+  const uint32_t s = seq % WgReduceLds<NB>::kSlots, turn = seq / WgReduceLds<NB>::kSlots;
+  // the slot may still serve an earlier band (only when a share spans more bands than there are slots)
   while (__hip_atomic_load(&red->gen[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) != turn)
     __builtin_amdgcn_s_sleep(2);
   for (;;) {
@@ -143,7 +146,7 @@ __device__ __forceinline__ bool wg_reduce_add(WgReduceLds<NB>* red, const float4
 template <int NB>
 __device__ __forceinline__ void wg_reduce_take(WgReduceLds<NB>* red, float4v (&acc)[kRowBlocks][NB], uint32_t seq,
                                                int lane) {
-  const uint32_t s = seq & 1u, turn = seq >> 1;
+  const uint32_t s = seq % WgReduceLds<NB>::kSlots, turn = seq / WgReduceLds<NB>::kSlots;
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
   float4v* d = &red->slot[s][lane];
 #pragma unroll
@@ -162,7 +165,7 @@ __device__ __forceinline__ void wg_reduce_take(WgReduceLds<NB>* red, float4v (&a
 // on the slot so that the turn count of later bands stays right.
 template <int NB>
 __device__ __forceinline__ void wg_reduce_skip(WgReduceLds<NB>* red, uint32_t seq, int lane) {
-  const uint32_t s = seq & 1u, turn = seq >> 1;
+  const uint32_t s = seq % WgReduceLds<NB>::kSlots, turn = seq / WgReduceLds<NB>::kSlots;
   while (__hip_atomic_load(&red->gen[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) != turn)
     __builtin_amdgcn_s_sleep(2);
   if (lane == 0) __hip_atomic_store(&red->gen[s], turn + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);

@@ -46,13 +46,20 @@ struct OffsetWindow {
   uint32_t window;  // this lane's offset
   int lane;
 
-  __device__ __forceinline__ void load(uint32_t t) {
+  // The two halves of a reload; between them the caller may do work that does not need the offsets.
+  __device__ __forceinline__ void request(uint32_t t) {
     base = t;
     const uint32_t idx = t + (uint32_t)lane;
     window = offs[idx < T ? idx : T];
+  }
+  __device__ __forceinline__ void arrive() {
     // Wait for the value here, inside the (rare) reload path: if its arrival were first needed
     // after the paths join, every tile would pay a full "wait for all loads".
     asm volatile("" : "+v"(window));
+  }
+  __device__ __forceinline__ void load(uint32_t t) {
+    request(t);
+    arrive();
   }
   // offsets of tiles t and t + 1 (reloads the window when t + 1 falls outside it)
   __device__ __forceinline__ void get(uint32_t t, uint32_t& begin, uint32_t& end) {
@@ -83,6 +90,12 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   const uint32_t t0 = (uint32_t)((uint64_t)g * T / G), t1 = (uint32_t)((uint64_t)(g + 1) * T / G);
   const uint32_t share0 = share_begin(blockIdx.x, T, gridDim.x), share1 = share_begin(blockIdx.x + 1, T, gridDim.x);
   constexpr int kWaveLds = wave_lds(NB);
+  // the first offsets are on their way while LDS is set up
+  OffsetWindow win;
+  win.offs = p.offs;
+  win.T = T;
+  win.lane = lane;
+  win.request(t0 < T ? t0 : T);
   WgReduceLds<NB>* red = (WgReduceLds<NB>*)(lds + WAVES * kWaveLds);
   wg_reduce_init<NB>(red, threadIdx.x, WAVES * 64);
   __syncthreads();  // the only barrier: from here on the waves run independently
@@ -103,11 +116,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 
   XFrags xf;
   xf.init(p.X, p.K, p.out.N, p.out.n0, lane);
-  OffsetWindow win;
-  win.offs = p.offs;
-  win.T = T;
-  win.lane = lane;
-  win.load(t0);
+  win.arrive();
   const unsigned char* frag = tile + ((lane >> 4) * kTileM + (lane & 15)) * 16;
 
   // A wave's run [t0, t1) is walked piece by piece, a piece being its tiles of one row band
@@ -223,20 +232,23 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   uint32_t sb[NS], se[NS];  // word range of the tile each stage holds
 
   auto step = [&](u32x4(&ss)[R], u32x4(&sx)[NB], uint32_t& b, uint32_t& e) {
-#ifdef FLS_PRIO_FLIP
-    // Two waves share a SIMD and the older one wins every issue slot when both are ready, so it
-    // would finish its run microseconds ahead of the younger.  Alternating the priority tile by
-    // tile gives both the same share of the SIMD.
-    if (((tc ^ (wave >> 2)) & 1u) != 0) __builtin_amdgcn_s_setprio(1);
-    else __builtin_amdgcn_s_setprio(0);
-#endif
+    // Two waves share a SIMD and, at equal priority, the older one wins every issue slot both
+    // want (LDS and memory instructions compete CU-wide), so it would finish its run microseconds
+    // ahead of the younger, which then runs the tail alone.  The younger waves sit at priority 1;
+    // the older ones alternate between 0 and 2 from tile to tile, so each side wins half the time.
+    if (WAVES > 4 && wave < WAVES / 2) {
+      if (tc & 1u) __builtin_amdgcn_s_setprio(2);
+      else __builtin_amdgcn_s_setprio(0);
+    }
     extract(ss, b, e);
     xf.template stage<NB>(xs, sx);
     issue(ss, sx, b, e);
     compute();
+    if (tc == t0) FLS_STAMP(p.out.flags, 512 + blockIdx.x, wave);  // debug builds: the wave's first tile is done
     ++tc;
   };
 
+  if (WAVES > 4 && wave >= WAVES / 2) __builtin_amdgcn_s_setprio(1);
   while (tc < t1) {
     const uint32_t piece0 = tc;
     pend = tc + (KT - ktc) < t1 ? tc + (KT - ktc) : t1;
@@ -273,7 +285,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 // per tile) get a deeper ring, as far as the registers allow: a stage costs 4 R + 4 NB registers,
 // the accumulators 32 NB, and a wave has 256 registers with eight waves per workgroup, 512 with four.
 #ifndef FLS_WIDE_WAVES
-#define FLS_WIDE_WAVES 0
+#define FLS_WIDE_WAVES 4
 #endif
 constexpr int ring_depth(int NB, int WAVES, int R) {
   if (NB == 4 && WAVES == 8) return R <= 2 ? 3 : 2;
