@@ -91,6 +91,8 @@ int num_cus() {
 int check_mm_args(const void* W, const void* X, void* C, int64_t M, int64_t K, int64_t N) {
   if (!W || !X || !C) return FLS_EINVAL;
   if (!shape_ok(M, K) || N < 1 || N > FLS_MAX_N) return FLS_EINVAL;
+  // X and C are addressed with 32-bit byte offsets through buffer descriptors
+  if ((uint64_t)K * (uint64_t)N * 2u > 0x7fffffffull || (uint64_t)M * (uint64_t)N * 2u > 0x7fffffffull) return FLS_EINVAL;
   if (!aligned16(W) || !aligned16(X) || !aligned16(C)) return FLS_EALIGN;
   return FLS_OK;
 }
@@ -100,8 +102,11 @@ int check_mm_args(const void* W, const void* X, void* C, int64_t M, int64_t K, i
 // every shape, so partial sums of one call can never be read as flags by the next.
 constexpr size_t kCounterAreaBytes = (size_t)4 << 20;
 uint32_t g_epoch = 0;  // launches since the workspace was registered; a flag equal to it is current
-void workspace_layout(int64_t N, size_t* total) {
-  *total = kCounterAreaBytes + fls::parts_floats((uint32_t)N) * sizeof(float);
+// then, for N > 32, X repacked into MFMA fragment order (K x N rounded up to 16 columns, fp16).
+void workspace_layout(int64_t K, int64_t N, size_t* total, size_t* xpack_offset) {
+  const size_t parts = fls::parts_floats((uint32_t)N) * sizeof(float);
+  if (xpack_offset) *xpack_offset = kCounterAreaBytes + parts;
+  *total = kCounterAreaBytes + parts + fls::xpack_bytes((uint32_t)K, (uint32_t)N);
 }
 
 }  // namespace
@@ -169,7 +174,7 @@ int fls_compress(const void* W_dev, int64_t M, int64_t K, void* out_dev, size_t 
 size_t fls_workspace_bytes(int64_t M, int64_t K, int64_t N) {
   if (!shape_ok(M, K) || N < 1 || N > FLS_MAX_N) return 0;
   size_t total;
-  workspace_layout(N, &total);
+  workspace_layout(K, N, &total, nullptr);
   return total;
 }
 
@@ -194,8 +199,8 @@ int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int6
              fls_stream_t stream) {
   int rc = check_mm_args(Wc_dev, X_dev, C_dev, M, K, N);
   if (rc != FLS_OK) return rc;
-  size_t need;
-  workspace_layout(N, &need);
+  size_t need, xpack_offset;
+  workspace_layout(K, N, &need, &xpack_offset);
   void* ws;
   uint32_t epoch0;
   BlobInfo info;
@@ -233,6 +238,7 @@ int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int6
   a.flags = (uint32_t*)ws;
   a.epoch0 = epoch0;
   a.parts = (float*)((unsigned char*)ws + kCounterAreaBytes);
+  a.xpack = (_Float16*)((unsigned char*)ws + xpack_offset);
   a.M = (uint32_t)M;
   a.K = (uint32_t)K;
   a.N = (uint32_t)N;
@@ -246,7 +252,7 @@ int fls_dense_gemm(const void* W_dev, const void* X_dev, void* C_dev, int64_t M,
   int rc = check_mm_args(W_dev, X_dev, C_dev, M, K, N);
   if (rc != FLS_OK) return rc;
   size_t need;
-  workspace_layout(N, &need);
+  workspace_layout(K, N, &need, nullptr);
   void* ws;
   uint32_t epoch0;
   {

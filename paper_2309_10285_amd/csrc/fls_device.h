@@ -365,4 +365,28 @@ struct XFrags {
   }
 };
 
+// The same fragments from a copy of X already in MFMA order: [K tile][column block][lane][8 halves],
+// made by xpack_kernel.  A column block of a tile is 1 KB of consecutive lanes, consecutive K tiles
+// follow each other, so every request is a full cache line and the fragment needs no transposition.
+struct XPacked {
+  __amdgpu_buffer_rsrc_t rsrc;
+  uint32_t lane_off;   // byte offset of this lane in the first column block of the launch
+  uint32_t tile_step;  // bytes per K tile (all column blocks)
+
+  __device__ __forceinline__ void init(const _Float16* Xp, uint32_t K, uint32_t N, uint32_t n0, int lane) {
+    const uint32_t blocks = (N + 15u) / 16u;
+    tile_step = blocks * 1024u;
+    rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)Xp, 0, (int)((K / kTileK) * tile_step), kBufferFlags);
+    lane_off = (n0 / 16u) * 1024u + (uint32_t)lane * 16u;
+  }
+  // column blocks past the last one of X read the next K tile's data (inside the buffer) or, in the
+  // last tile, zeros; their products land in accumulators that are never stored
+  template <int NB>
+  __device__ __forceinline__ void load(u32x4 (&x)[NB], uint32_t kt) const {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+      x[nb] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane_off + nb * 1024u, kt * tile_step, 0);
+  }
+};
+
 }  // namespace fls

@@ -12,6 +12,7 @@ struct SpmmLaunch {
   _Float16* C;
   float* parts;
   uint32_t* flags;
+  _Float16* xpack;  // workspace area of xpack_bytes(K, N) for X in MFMA fragment order (used when N > 32)
   uint32_t epoch0;  // launch number of the first column group (the next groups count on)
   uint32_t M, K, N;
   uint32_t max_tile_words;
@@ -49,6 +50,12 @@ constexpr uint32_t kMaxWorkgroups = 512;    // must equal fls::kMaxGrid of the d
 // fp32 values of the split-K partial slots: [workgroup][column blocks][128 x 16]
 inline size_t parts_floats(uint32_t N) {
   return (size_t)kMaxWorkgroups * group_blocks(N < kSpmmGroupCols ? N : kSpmmGroupCols) * 2048;
+}
+
+// Workspace bytes for X repacked into MFMA fragment order, [K tile][column block][lane][8 halves]
+// (the sparse kernel's wide variant reads it instead of X; narrower calls do not need it).
+inline size_t xpack_bytes(uint32_t K, uint32_t N) {
+  return N > kGroupCols ? (size_t)K * ((N + 15u) / 16u * 16u) * 2u : 0;
 }
 
 // Number of workgroups for a matrix of `bands` row bands on `cus` compute units (one workgroup

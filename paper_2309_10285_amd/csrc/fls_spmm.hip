@@ -25,13 +25,14 @@
 
 namespace fls {
 
-// LDS of one wave: its tile, the 16 B slot that padding words land in, the X stage (1 KB per column block)
-constexpr int wave_lds(int NB) { return kTileBytes + 16 + NB * 1024; }
+// LDS of one wave: its tile, the 16 B slot that padding words land in, and - unless X comes
+// repacked - the X stage (1 KB per column block)
+constexpr int wave_lds(int NB, bool wide) { return kTileBytes + 16 + (wide ? 0 : NB * 1024); }
 
 struct SpmmParams {
   const uint32_t* offs;   // TileOffsets
   const uint32_t* words;  // NonZeros
-  const _Float16* X;
+  const _Float16* X;      // X, or its repacked copy for the wide variant
   uint32_t K;
   OutParams out;
 };
@@ -80,7 +81,25 @@ __device__ __noinline__ void extract_overflow(const uint32_t* words, uint32_t be
   }
 }
 
-template <int NB, int WAVES, int R, int NS>
+// X in MFMA fragment order: block (K tile kt, column block nb) holds, for lane l = 16 g + c, the 8
+// halves X[32 kt + 8 g .. +7][16 nb + c] (zeros for columns past N).  One wave per block; loads are
+// quad-contiguous (lane j reads column j >> 2, chunk j & 3), stores go to the fragment position.
+__global__ __launch_bounds__(256) void xpack_kernel(const _Float16* X, _Float16* Xp, uint32_t K, uint32_t N, uint32_t units,
+                                                    uint32_t blocks) {
+  const uint32_t u = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (u >= units) return;
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t kt = u / blocks, nb = u - kt * blocks;
+  const uint32_t c = lane >> 2, g = lane & 3u;
+  const uint32_t col = nb * 16u + c;
+  u32x4 v = {0u, 0u, 0u, 0u};
+  if (col < N) v = *(const u32x4*)(X + (size_t)col * K + kt * kTileK + g * 8u);
+  *(u32x4*)(Xp + ((size_t)u * 64u + g * 16u + c) * 8u) = v;
+}
+
+// WIDE: the variant for more than 32 columns - four waves per workgroup (one per SIMD, each with
+// the whole register file), X read from its repacked copy, tiles software-pipelined inside a wave.
+template <int NB, int WAVES, int R, int NS, bool WIDE>
 __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   extern __shared__ __align__(16) unsigned char lds[];
   const int lane = threadIdx.x & 63;
@@ -89,7 +108,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   const uint32_t T = p.out.T, KT = p.out.KT;
   const uint32_t t0 = (uint32_t)((uint64_t)g * T / G), t1 = (uint32_t)((uint64_t)(g + 1) * T / G);
   const uint32_t share0 = share_begin(blockIdx.x, T, gridDim.x), share1 = share_begin(blockIdx.x + 1, T, gridDim.x);
-  constexpr int kWaveLds = wave_lds(NB);
+  constexpr int kWaveLds = wave_lds(NB, WIDE);
   // the first offsets are on their way while LDS is set up
   OffsetWindow win;
   win.offs = p.offs;
@@ -114,7 +133,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[rb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
 
-  XFrags xf;
+  typename std::conditional<WIDE, XPacked, XFrags>::type xf;
   xf.init(p.X, p.K, p.out.N, p.out.n0, lane);
   win.arrive();
   const unsigned char* frag = tile + ((lane >> 4) * kTileM + (lane & 15)) * 16;
@@ -135,7 +154,10 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     win.get(ti, begin, end);
     uint32_t n = end - begin;
     if (n > R * 256u) n = R * 256u;
-    if (ti >= pend) n = 0;
+    if (ti >= pend) {
+      n = 0;
+      end = begin;  // nothing to extract either
+    }
     const __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void*)(p.words + begin), 0, (int)(n * 4u), kBufferFlags);
 #pragma unroll
@@ -154,7 +176,18 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const uint32_t q = r * 64 + lane;
-      if (q * 4 < n) {
+      if constexpr (WIDE) {
+        // branch-free, so that the whole step is one basic block and the scheduler may spread the
+        // MFMAs of the previous tile between these stores: lanes past the end of the run (their
+        // loads returned 0) are pointed at the slot that padding words go to
+        const bool valid = q * 4 < n;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t w = valid ? s[r][j] : (uint32_t)kTileElems;
+          if (FLS_ABLATE & 4) asm volatile("" ::"v"(w));
+          else *(uint16_t*)(tile + ((w & 0xffffu) << 1)) = (uint16_t)(w >> 16);
+        }
+      } else if (q * 4 < n) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const uint32_t w = s[r][j];
@@ -166,15 +199,35 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     if (n > R * 256u) extract_overflow(p.words, begin + R * 256u, end, tile);
   };
 
-  // smem2tc + rst_smem.  All fragment reads are issued first and the re-zeroing right behind
-  // them: the LDS runs a wave's operations in order, so the zeros cannot overtake the reads, and
-  // the MFMAs then wait for the reads only.
+  auto read_frags = [&](half8(&a)[kRowBlocks]) {
+#pragma unroll
+    for (int j = 0; j < kRowBlocks; ++j) {
+      if (FLS_ABLATE & 16) a[j] = half8{1, 1, 1, 1, 1, 1, 1, 1};
+      else a[j] = *(const half8*)(frag + j * 256);
+    }
+    if (!(FLS_ABLATE & 8)) {
+#pragma unroll
+      for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
+    }
+  };
+  auto mfma = [&](const half8(&a)[kRowBlocks], const half8(&b)[NB]) {
+#pragma unroll
+    for (int j = 0; j < kRowBlocks; ++j) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        if (FLS_ABLATE & 2) acc[j][nb][0] += (float)a[j][0] * (float)b[nb][0];
+        else acc[j][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[j], b[nb], acc[j][nb], 0, 0, 0);
+      }
+    }
+  };
   auto compute = [&]() {
     half8 x[NB];
+    if constexpr (!WIDE) {
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) x[nb] = xf.frag(xs, nb);
+      for (int nb = 0; nb < NB; ++nb) x[nb] = xf.frag(xs, nb);
+    }
     // fragments of H row blocks at a time (all eight when the accumulators leave the registers for it)
-    constexpr int H = (NB == 1 || WAVES <= 4) ? 8 : (NB == 2 ? 4 : 2);
+    constexpr int H = NB == 1 ? 8 : (NB == 2 ? 4 : 2);
 #pragma unroll
     for (int h = 0; h < kRowBlocks; h += H) {
       half8 a[H];
@@ -241,10 +294,38 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
       else __builtin_amdgcn_s_setprio(0);
     }
     extract(ss, b, e);
-    xf.template stage<NB>(xs, sx);
+    if constexpr (!WIDE) xf.template stage<NB>(xs, sx);
     issue(ss, sx, b, e);
     compute();
     if (tc == t0) FLS_STAMP(p.out.flags, 512 + blockIdx.x, wave);  // debug builds: the wave's first tile is done
+    ++tc;
+  };
+
+  // With one wave per SIMD (the wide variant) nothing else fills a wave's waits, so its tiles are
+  // software-pipelined: a step first reads the fragments of its tile, which the step before put
+  // into LDS, then extracts the NEXT tile behind those reads, and only then runs the MFMAs - the
+  // LDS latency of the fragment reads passes during the extraction, and the extraction's
+  // instructions issue in the shadow of the MFMAs.  `ss`, `sx` are the stage of the next tile; xb
+  // carries a tile's X fragments from the step that frees their stage to the step that uses them.
+  half8 xb[NB];
+  auto step_pipelined = [&](u32x4(&ss)[R], u32x4(&sx)[NB], uint32_t& b, uint32_t& e) {
+    half8 fa[kRowBlocks], fb[NB];
+    read_frags(fa);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) fb[nb] = xb[nb];
+    extract(ss, b, e);  // empty past the end of the piece
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) xb[nb] = __builtin_bit_cast(half8, sx[nb]);
+    issue(ss, sx, b, e);
+    mfma(fa, fb);
+    // asks the scheduler for: one MFMA, then up to three instructions of the other kinds (VALU,
+    // SALU, memory, LDS), 8 * NB times over
+#pragma unroll
+    for (int i = 0; i < kRowBlocks * NB; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002 | 0x004 | 0x010 | 0x080, 3, 0);
+    }
+    if (tc == t0) FLS_STAMP(p.out.flags, 512 + blockIdx.x, wave);
     ++tc;
   };
 
@@ -256,13 +337,27 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     kti = ktc;
 #pragma unroll
     for (int i = 0; i < NS; ++i) issue(s[i], x[i], sb[i], se[i]);
-    while (tc + NS <= pend) {
+    if constexpr (WIDE) {
+      extract(s[0], sb[0], se[0]);
 #pragma unroll
-      for (int i = 0; i < NS; ++i) step(s[i], x[i], sb[i], se[i]);
+      for (int nb = 0; nb < NB; ++nb) xb[nb] = __builtin_bit_cast(half8, x[0][nb]);
+      issue(s[0], x[0], sb[0], se[0]);
+      while (tc + NS <= pend) {
+#pragma unroll
+        for (int i = 0; i < NS; ++i) step_pipelined(s[(i + 1) % NS], x[(i + 1) % NS], sb[(i + 1) % NS], se[(i + 1) % NS]);
+      }
+#pragma unroll
+      for (int i = 0; i < NS - 1; ++i)
+        if (tc < pend) step_pipelined(s[(i + 1) % NS], x[(i + 1) % NS], sb[(i + 1) % NS], se[(i + 1) % NS]);
+    } else {
+      while (tc + NS <= pend) {
+#pragma unroll
+        for (int i = 0; i < NS; ++i) step(s[i], x[i], sb[i], se[i]);
+      }
+#pragma unroll
+      for (int i = 0; i < NS - 1; ++i)
+        if (tc < pend) step(s[i], x[i], sb[i], se[i]);
     }
-#pragma unroll
-    for (int i = 0; i < NS - 1; ++i)
-      if (tc < pend) step(s[i], x[i], sb[i], se[i]);
     hand_over(bandc, pend - piece0);
     ktc += pend - piece0;
     if (ktc == KT) {
@@ -284,11 +379,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 // wave (80 KB per CU) covers the latency of HBM, so sparser matrices (fewer rounds R of 256 words
 // per tile) get a deeper ring, as far as the registers allow: a stage costs 4 R + 4 NB registers,
 // the accumulators 32 NB, and a wave has 256 registers with eight waves per workgroup, 512 with four.
-#ifndef FLS_WIDE_WAVES
-#define FLS_WIDE_WAVES 4
-#endif
 constexpr int ring_depth(int NB, int WAVES, int R) {
-  if (NB == 4 && WAVES == 8) return R <= 2 ? 3 : 2;
   if (WAVES <= 4) return R <= 2 ? 8 : (R <= 4 ? 6 : (R <= 6 ? 4 : 3));
   if (NB == 1) return FLS_NSTAGE;
   return R <= 2 ? 4 : 2;
@@ -297,15 +388,16 @@ constexpr int ring_depth(int NB, int WAVES, int R) {
 template <int NB, int WAVES, int R>
 static hipError_t launch_variant(const SpmmParams& p, int grid, hipStream_t stream) {
   constexpr int NS = ring_depth(NB, WAVES, R);
+  constexpr bool WIDE = WAVES <= 4;
   static bool attr_done = false;
-  const int lds_bytes = WAVES * wave_lds(NB) + (int)sizeof(WgReduceLds<NB>);
+  const int lds_bytes = WAVES * wave_lds(NB, WIDE) + (int)sizeof(WgReduceLds<NB>);
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)spmm_kernel<NB, WAVES, R, NS>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    hipError_t e = hipFuncSetAttribute((const void*)spmm_kernel<NB, WAVES, R, NS, WIDE>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        lds_bytes);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL((spmm_kernel<NB, WAVES, R, NS>), dim3(grid), dim3(WAVES * 64), lds_bytes, stream, p);
+  hipLaunchKernelGGL((spmm_kernel<NB, WAVES, R, NS, WIDE>), dim3(grid), dim3(WAVES * 64), lds_bytes, stream, p);
   return hipGetLastError();
 }
 
@@ -339,6 +431,13 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
   if (a.max_tile_words <= 2 * 256) R = 2;
   else if (a.max_tile_words <= 4 * 256) R = 4;
   else if (a.max_tile_words <= 6 * 256) R = 6;
+  if (a.N > kGroupCols) {
+    // the wide variant reads X from a copy in MFMA fragment order, made once per call
+    const uint32_t blocks = (a.N + 15u) / 16u, units = p.out.KT * blocks;
+    hipLaunchKernelGGL(xpack_kernel, dim3((units + 3) / 4), dim3(256), 0, stream, a.X, a.xpack, a.K, a.N, units, blocks);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   uint32_t launches = 0;
   for (uint32_t n0 = 0; n0 < a.N;) {
     p.out.n0 = n0;
@@ -346,13 +445,16 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
     const uint32_t left = a.N - n0;
     hipError_t e;
     if (left <= 16) {
+      p.X = a.X;
       e = launch_r<1, 8>(R, p, grid, stream);
       n0 += 16;
-    } else if (left <= 32 || FLS_WIDE_WAVES == 0) {
+    } else if (left <= 32) {
+      p.X = a.X;
       e = launch_r<2, 8>(R, p, grid, stream);
       n0 += 32;
     } else {
-      e = launch_r<4, FLS_WIDE_WAVES ? FLS_WIDE_WAVES : 4>(R, p, grid, stream);
+      p.X = a.xpack;
+      e = launch_r<4, 4>(R, p, grid, stream);
       n0 += kSpmmGroupCols;
     }
     if (e != hipSuccess) return e;
