@@ -199,13 +199,33 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     if (n > R * 256u) extract_overflow(p.words, begin + R * 256u, end, tile);
   };
 
+  // rst_smem for sparse tiles: instead of zeroing all 8 KB (eight 16 B stores per lane, 64 LDS
+  // clocks), store a zero at the places the tile's words went to - the same count of 2 B stores
+  // as the extraction, which is less LDS time as long as a tile has at most about 1000 words.
+  constexpr bool kUnscatter = !WIDE && R <= 4;
+  auto unscatter = [&](const u32x4(&s)[R], uint32_t begin, uint32_t end) {
+    const uint32_t n = end - begin;
+    if (n > R * 256u) {  // the overflow path wrote words this wave no longer holds
+#pragma unroll
+      for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
+    } else {
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const uint32_t q = r * 64 + lane;
+        if (q * 4 < n) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) *(uint16_t*)(tile + ((s[r][j] & 0xffffu) << 1)) = (uint16_t)0;
+        }
+      }
+    }
+  };
   auto read_frags = [&](half8(&a)[kRowBlocks]) {
 #pragma unroll
     for (int j = 0; j < kRowBlocks; ++j) {
       if (FLS_ABLATE & 16) a[j] = half8{1, 1, 1, 1, 1, 1, 1, 1};
       else a[j] = *(const half8*)(frag + j * 256);
     }
-    if (!(FLS_ABLATE & 8)) {
+    if (!kUnscatter && !(FLS_ABLATE & 8)) {
 #pragma unroll
       for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
     }
@@ -295,8 +315,18 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     }
     extract(ss, b, e);
     if constexpr (!WIDE) xf.template stage<NB>(xs, sx);
-    issue(ss, sx, b, e);
-    compute();
+    if constexpr (kUnscatter) {
+      half8 fa[kRowBlocks], fb[NB];
+      read_frags(fa);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) fb[nb] = xf.frag(xs, nb);
+      if (!(FLS_ABLATE & 8)) unscatter(ss, b, e);  // behind the reads: LDS keeps a wave's operations in order
+      issue(ss, sx, b, e);
+      mfma(fa, fb);
+    } else {
+      issue(ss, sx, b, e);
+      compute();
+    }
     if (tc == t0) FLS_STAMP(p.out.flags, 512 + blockIdx.x, wave);  // debug builds: the wave's first tile is done
     ++tc;
   };
