@@ -42,6 +42,64 @@ def _time_loop(fn, copies, steps, warmup):
     return e0.elapsed_time(e1) / steps, host_ms / steps
 
 
+def run_sweep(args):
+    """The sparsity x mask x N sweep on the 12288 x 12288 matrix: one JSON line per point (not the bench line)."""
+    import torch
+
+    import fls_workloads as wl
+    import oracle
+    import paper_2309_10285_amd as fls
+
+    fls.lib()
+    M, K = wl.SWEEP_M, wl.SWEEP_K
+    W32 = wl.gen_weights_f32(M, K, wl.SWEEP_SEED)
+    rows = 256  # rows of C checked against the oracle at every point
+    out = open(args.out, "w") if args.out else None
+
+    def emit(rec):
+        line = json.dumps(rec)
+        print(line, flush=True)
+        if out:
+            out.write(line + "\n")
+            out.flush()
+
+    Xs = {N: wl.gen_x(N, K, wl.SWEEP_SEED + 2) for N in wl.SWEEP_NS}
+    Xd = {N: torch.from_numpy(Xs[N].view(np.float16)).cuda() for N in wl.SWEEP_NS}
+    fls.ensure_workspace(M, K, max(wl.SWEEP_NS))
+    Wd = torch.from_numpy(wl.dense_bits(W32).view(np.float16)).cuda()
+    dense = [Wd, Wd.clone(), Wd.clone(), Wd.clone()]
+    dense_ms = {}
+    for N in wl.SWEEP_NS:
+        D = torch.empty((N, M), dtype=torch.float16, device="cuda")
+        dense_ms[N], _ = _time_loop(lambda w: fls.fls_dense_gemm(w, Xd[N], D, M, K, N), dense, args.steps, args.warmup)
+        emit({"point": f"dense-N{N}", "N": N, "us": round(dense_ms[N] * 1e3, 2),
+              "GBps": round((2 * M * K + 2 * K * N + 2 * M * N) / dense_ms[N] / 1e6, 1)})
+    del dense, Wd
+    for mask in wl.SWEEP_MASKS:
+        for beta in wl.SWEEP_BETAS:
+            cfg = wl.sweep_config(beta, mask, 8)
+            Wb = (wl.prune_uniform if mask == "uniform" else wl.prune_row_skewed)(W32, beta, wl.SWEEP_SEED + 1)
+            W = torch.from_numpy(Wb.view(np.float16)).cuda()
+            blob0, st = fls.fls_compress(W)
+            blob0 = blob0.clone()
+            del W
+            n_copies = max(2, -(-MIN_ROTATION_BYTES // st["bytes_total"]))
+            blobs = [blob0] + [blob0.clone() for _ in range(n_copies - 1)]
+            for N in wl.SWEEP_NS:
+                C = torch.empty((N, M), dtype=torch.float16, device="cuda")
+                ms, _ = _time_loop(lambda b: fls.fls_spmm(b, Xd[N], C, M, K, N), blobs, args.steps, args.warmup)
+                ref = oracle.ref_spmm_f64(Wb, Xs[N], rows=(0, rows))
+                got = C.cpu().numpy()[:, :rows].astype(np.float64)
+                err = float(np.abs(got - ref[:, :rows]).max() / np.abs(ref[:, :rows]).max())
+                alg = st["bytes_total"] + 2 * K * N + 2 * M * N
+                emit({"point": f"{mask}-{int(round(beta * 100))}-N{N}", "mask": mask, "sparsity": beta, "N": N,
+                      "nnz": st["nnz"], "max_tile_words": st["max_tile_words"], "us": round(ms * 1e3, 2),
+                      "TFLOPs": round(2.0 * M * K * N / ms / 1e9, 1), "GBps": round(alg / ms / 1e6, 1),
+                      "hbm_frac": round(alg / ms / 1e6 / HBM_PEAK_GBS, 4), "speedup_vs_dense": round(dense_ms[N] / ms, 3),
+                      "max_rel_err_first_256_rows": err})
+            del blobs, blob0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -50,12 +108,19 @@ def main():
     ap.add_argument("--config", default="C2", help="C1..C4 (C2 is the configuration the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the bench line: the 12288 x 12288 sweep (sparsity x mask x N, each with its dense pair)")
+    ap.add_argument("--out", default="", help="with --sweep: also write the lines to this file")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (the known-size kernel the HBM counters "
                          "of a rocprofv3 --pmc run are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is a one-GPU kernel path (no sharding, no collectives); run with --gpus 1")
+
+    if args.sweep:
+        run_sweep(args)
+        return
 
     import torch
 
@@ -88,7 +153,7 @@ def main():
     C_host = C.cpu().numpy()
 
     out = {
-        "metric": "SpMM dense-equivalent TFLOP/s (2*M*K*N / latency), OPT-30B-shaped FFN up-projection, 80 % sparsity, N=16",
+        "metric": f"SpMM dense-equivalent TFLOP/s (2*M*K*N / latency), {cfg.what}, {int(cfg.beta * 100)} % sparsity, N={N}",
         "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",

@@ -225,6 +225,7 @@ __device__ __forceinline__ void owner_finish(const OutParams& o, float4v (&acc)[
       }
     }
   }
+  FLS_STAMP(o.flags, wg, 6);
   // As many loads as the registers allow are issued before the first is used: each is a trip
   // to memory, and this runs when the kernel is about to end, with nothing left to hide it behind.
   constexpr int kBatch = NB == 1 ? 4 : (NB == 2 ? 2 : 3);  // slots in flight (four column blocks: the wide variant, 512 registers)
@@ -313,8 +314,16 @@ __device__ __forceinline__ void hand_over_piece(const OutParams& o, WgReduceLds<
 template <int NB>
 __device__ __forceinline__ void hand_over_finish(const OutParams& o, float4v (&acc)[kRowBlocks][NB],
                                                  const HandoverState& st, uint32_t wg, uint32_t P, int lane) {
-  if (st.publish) publish_partial(o, wg, lane);
-  if (st.own) owner_finish<NB>(o, acc, st.own_band, wg, P, lane);
+  if (st.publish) {
+    FLS_STAMP(o.flags, wg, 3);
+    publish_partial(o, wg, lane);
+    FLS_STAMP(o.flags, wg, 4);
+  }
+  if (st.own) {
+    FLS_STAMP(o.flags, wg, 5);
+    owner_finish<NB>(o, acc, st.own_band, wg, P, lane);
+    FLS_STAMP(o.flags, wg, 7);
+  }
 }
 
 // B operand fragments (X) of one K tile.  An MFMA wants lane l to hold column (l & 15) and the 8

@@ -50,6 +50,9 @@ def test_argument_errors_need_no_device(fls):
     assert L.fls_spmm(16, 16, 16, 128, 32, 0, None) == fls.EINVAL
     assert L.fls_spmm(16, 16, 16, 128, 32, 257, None) == fls.EINVAL
     assert L.fls_spmm(16, 16, 16, 127, 32, 8, None) == fls.EINVAL
+    # X (K x N fp16) and C are addressed with 32-bit byte offsets: 2 K N and 2 M N must stay below 2^31
+    assert L.fls_spmm(16, 16, 16, 128, 1 << 23, 256, None) == fls.EINVAL
+    assert L.fls_dense_gemm(16, 16, 16, 128 << 16, 32, 256, None) == fls.EINVAL
     assert L.fls_spmm(16, 8, 16, 128, 32, 8, None) == fls.EALIGN
     assert L.fls_spmm(16, 16, 16, 128, 32, 8, None) == fls.EWORKSPACE   # nothing registered
     assert L.fls_dense_gemm(16, 16, 16, 128, 32, 8, None) == fls.EWORKSPACE

@@ -137,8 +137,9 @@ def test_spmm_matches_oracle(fls, oracle_mod, name, W, N):
     assert _rel_err(C, ref) <= TOL
 
 
-@pytest.mark.parametrize("N", [100, 128, 256])
+@pytest.mark.parametrize("N", [33, 48, 80, 96, 100, 128, 256])
 def test_spmm_wide_n(fls, oracle_mod, N):
+    # column groups: 64-column passes (X repacked into fragment order) followed by a 16- or 32-column rest
     W = CASES[3][1]
     M, K = W.shape
     X = wl.gen_x(N, K, 5)
@@ -242,3 +243,56 @@ def test_error_codes_on_device(fls):
     assert rc == fls.EFORMAT  # header says 128 rows
     rc = fls.lib().fls_spmm(blob.data_ptr() + 2, X.data_ptr(), C.data_ptr(), 128, 32, 8, None)
     assert rc == fls.EALIGN
+
+
+def test_spmm_wide_n_split_bands(fls, oracle_mod):
+    # few bands, long K: every band is cut between workgroups, so the 64-column pass hands 32 KB partial sums over
+    W = wl.prune_uniform(wl.gen_weights_f32(384, 8192, 11), 0.9, 12)
+    for N in (64, 72):
+        X = wl.gen_x(N, 8192, 13)
+        _, _, C = _run_spmm(fls, W, X, N)
+        assert _rel_err(C, oracle_mod.ref_spmm_f64(W, X)) <= TOL
+
+
+def test_full_size_c2_sampled_rows_and_blob(fls, oracle_mod):
+    """The benchmark configuration itself (W 28672 x 7168, 80 % magnitude-pruned, N = 16), as bench.py launches it:
+    the whole blob against the oracle's, and C on sampled row bands (first, two inner, last) that the oracle
+    computes row by row."""
+    cfg = wl.CONFIGS["C2"]
+    W, X = wl.make_inputs(cfg)
+    blob, st, C = _run_spmm(fls, W, X, cfg.N)
+    ref_blob = oracle_mod.ref_compress(W)
+    assert st["bytes_total"] == ref_blob.size
+    assert np.array_equal(blob.cpu().numpy(), ref_blob)
+    for band in (0, 77, 150, cfg.M // 128 - 1):
+        m0, m1 = band * 128, band * 128 + 128
+        ref = oracle_mod.ref_spmm_f64(W, X, rows=(m0, m1))[:, m0:m1]
+        assert _rel_err(C[:, m0:m1], ref) <= TOL
+
+
+def test_back_to_back_shapes_share_one_workspace(fls, oracle_mod):
+    """Calls of different shapes and widths, alternating, on one registered workspace: epochs advance per launch,
+    nothing is cleared in between, and the kernels' error word (a hand-over wait that gave up) stays 0."""
+    import torch
+
+    work = []
+    for (name, W), N in zip([CASES[3], CASES[4], CASES[7], CASES[1]], [16, 64, 32, 80]):
+        M, K = W.shape
+        X = wl.gen_x(N, K, 21 + N)
+        work.append((W, X, N, oracle_mod.ref_spmm_f64(W, X)))
+    fls.ensure_workspace(2048, 2048, 256)  # large enough for all of them
+    ws = fls._ws_tensor
+    blobs = [fls.fls_compress(_dev_w(W))[0] for W, _, _, _ in work]
+    for rep in range(3):
+        for (W, X, N, ref), blob in zip(work, blobs):
+            M, K = W.shape
+            Xd = torch.from_numpy(X.view(np.float16)).cuda()
+            C = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+            fls.fls_spmm(blob, Xd, C, M, K, N)
+            D = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+            fls.fls_dense_gemm(_dev_w(W), Xd, D, M, K, N)
+            torch.cuda.synchronize()
+            assert _rel_err(C.cpu().numpy(), ref) <= TOL
+            assert _rel_err(D.cpu().numpy(), ref) <= TOL
+    assert fls._ws_tensor is ws  # still the same registration
+    assert int(ws[512 * 4:512 * 4 + 4].cpu().numpy().view(np.uint32)[0]) == 0  # error word: flags[512]
