@@ -5,8 +5,8 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libfls.so")
-SOURCES = ["fls_api.hip", "fls_spmm.hip", "fls_dense.hip", "fls_compress.hip"]
-HEADERS = ["fls_device.h", "fls_launch.h", os.path.join("..", "..", "include", "fls.h")]
+SOURCES = ["fls_api.hip", "fls_spmm.hip", "fls_spmm_wide.hip", "fls_dense.hip", "fls_compress.hip"]
+HEADERS = ["fls_device.h", "fls_launch.h", "fls_tile.h", os.path.join("..", "..", "include", "fls.h")]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-munsafe-fp-atomics",

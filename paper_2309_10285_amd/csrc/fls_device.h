@@ -228,7 +228,7 @@ __device__ __forceinline__ void owner_finish(const OutParams& o, float4v (&acc)[
   FLS_STAMP(o.flags, wg, 6);
   // As many loads as the registers allow are issued before the first is used: each is a trip
   // to memory, and this runs when the kernel is about to end, with nothing left to hide it behind.
-  constexpr int kBatch = NB == 1 ? 4 : (NB == 2 ? 2 : 3);  // slots in flight (four column blocks: the wide variant, 512 registers)
+  constexpr int kBatch = NB == 1 ? 4 : (NB == 2 ? 2 : 1);  // slots in flight
   constexpr int kBlocks = NB == 4 ? 2 : NB;                 // column blocks of a slot in flight
   uint32_t q = wg + 1;
   while (q < P && share_begin(q, o.T, P) < band_hi) {
@@ -371,30 +371,6 @@ struct XFrags {
   // MFMA B fragment of column block nb
   __device__ __forceinline__ half8 frag(const unsigned char* xs, int nb) const {
     return *(const half8*)(xs + nb * 1024 + rslot);
-  }
-};
-
-// The same fragments from a copy of X already in MFMA order: [K tile][column block][lane][8 halves],
-// made by xpack_kernel.  A column block of a tile is 1 KB of consecutive lanes, consecutive K tiles
-// follow each other, so every request is a full cache line and the fragment needs no transposition.
-struct XPacked {
-  __amdgpu_buffer_rsrc_t rsrc;
-  uint32_t lane_off;   // byte offset of this lane in the first column block of the launch
-  uint32_t tile_step;  // bytes per K tile (all column blocks)
-
-  __device__ __forceinline__ void init(const _Float16* Xp, uint32_t K, uint32_t N, uint32_t n0, int lane) {
-    const uint32_t blocks = (N + 15u) / 16u;
-    tile_step = blocks * 1024u;
-    rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)Xp, 0, (int)((K / kTileK) * tile_step), kBufferFlags);
-    lane_off = (n0 / 16u) * 1024u + (uint32_t)lane * 16u;
-  }
-  // column blocks past the last one of X read the next K tile's data (inside the buffer) or, in the
-  // last tile, zeros; their products land in accumulators that are never stored
-  template <int NB>
-  __device__ __forceinline__ void load(u32x4 (&x)[NB], uint32_t kt) const {
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-      x[nb] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane_off + nb * 1024u, kt * tile_step, 0);
   }
 };
 

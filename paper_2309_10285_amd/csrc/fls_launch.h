@@ -37,19 +37,31 @@ struct CompressLaunch {
   uint32_t policy;
 };
 
-// Columns are processed in groups, one launch per group (each streams W again); a group runs as
-// 1, 2 or 4 MFMA column blocks of 16.  The dense baseline takes groups of up to kGroupCols columns.
-// The sparse kernel takes up to kSpmmGroupCols: its four-block variant runs four waves per
-// workgroup instead of eight, so that a wave may use the whole register file of its SIMD
-// (128 accumulator registers and a deep load ring do not fit in half of it).
+// Columns are processed in groups, one pass over W per group.  The dense baseline and the sparse
+// kernel's narrow variants take up to kGroupCols columns (1 or 2 MFMA column blocks of 16 per
+// wave); more than that goes to the sparse kernel's 64-column pass (four column blocks, four waves
+// per workgroup with the whole register file each).
 constexpr uint32_t kGroupCols = 32;
 constexpr uint32_t kSpmmGroupCols = 64;
 inline uint32_t column_groups(uint32_t N) { return (N + kGroupCols - 1) / kGroupCols; }  // upper bound on launches per call
 inline uint32_t group_blocks(uint32_t ncols) { return ncols <= 16 ? 1u : (ncols <= 32 ? 2u : 4u); }
 constexpr uint32_t kMaxWorkgroups = 512;    // must equal fls::kMaxGrid of the device code
-// fp32 values of the split-K partial slots: [workgroup][column blocks][128 x 16]
+// The 64-column pass of the sparse kernel cuts its work as (group of 4 bands) x (K slice) and
+// keeps one 128 x 64 fp32 partial result per band and slice.  Slices per group: as many as fill
+// the CUs, but none shorter than 16 tiles.  groups * slices <= kMaxWorkgroups, so bands * slices
+// <= 4 * kMaxWorkgroups partial results at most.
+inline uint32_t wide_slices(uint32_t bands, uint32_t KT, int cus) {
+  if (cus > (int)kMaxWorkgroups) cus = (int)kMaxWorkgroups;
+  const uint32_t groups = (bands + 3) / 4;
+  uint32_t S = groups < (uint32_t)cus ? (uint32_t)cus / groups : 1u;
+  const uint32_t by_length = KT / 16u > 0 ? KT / 16u : 1u;
+  return S < by_length ? S : by_length;
+}
+// fp32 values of the split-K partial sums: [workgroup][column blocks][128 x 16] for the passes of
+// up to 32 columns, [band][slice][4][128 x 16] for the 64-column pass
 inline size_t parts_floats(uint32_t N) {
-  return (size_t)kMaxWorkgroups * group_blocks(N < kSpmmGroupCols ? N : kSpmmGroupCols) * 2048;
+  if (N > kGroupCols) return (size_t)4 * kMaxWorkgroups * 4 * 2048;
+  return (size_t)kMaxWorkgroups * group_blocks(N) * 2048;
 }
 
 // Workspace bytes for X repacked into MFMA fragment order, [K tile][column block][lane][8 halves]
@@ -74,6 +86,9 @@ inline int pick_grid(uint32_t bands, int cus) {
 }
 
 hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream);
+// X -> a.xpack (fragment order), then one 64-column pass per call of launch_spmm_wide from column n0 on
+hipError_t launch_xpack(const SpmmLaunch& a, hipStream_t stream);
+hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, hipStream_t stream);
 hipError_t launch_dense(const DenseLaunch& a, hipStream_t stream);
 // phase 1: per-tile counts, prefix sums, header (everything but the words)
 hipError_t launch_compress_index(const CompressLaunch& a, hipStream_t stream);

@@ -15,6 +15,7 @@
 // bands are summed in LDS inside a workgroup and through fp32 slots in HBM between workgroups.
 #include "fls_device.h"
 #include "fls_launch.h"
+#include "fls_tile.h"
 
 // Latency-breakdown builds (the paper's Fig. 11 method: erase the other operations and time what is
 // left).  FLS_ABLATE is a bit mask, 0 in the library: 1 no split-K hand-over, 2 no MFMA, 4 no extract,
@@ -25,9 +26,8 @@
 
 namespace fls {
 
-// LDS of one wave: its tile, the 16 B slot that padding words land in, and - unless X comes
-// repacked - the X stage (1 KB per column block)
-constexpr int wave_lds(int NB, bool wide) { return kTileBytes + 16 + (wide ? 0 : NB * 1024); }
+// LDS of one wave: its tile, the 16 B slot that padding words land in, the X stage (1 KB per column block)
+constexpr int wave_lds(int NB) { return kTileBytes + 16 + NB * 1024; }
 
 struct SpmmParams {
   const uint32_t* offs;   // TileOffsets
@@ -37,69 +37,7 @@ struct SpmmParams {
   OutParams out;
 };
 
-// TileOffsets of 64 consecutive tiles, one per lane of a VGPR, picked with v_readlane: stepping
-// to the next tile then costs no memory access (a load per tile, scalar or vector, would put its
-// latency on the critical path of every tile).
-struct OffsetWindow {
-  const uint32_t* offs;
-  uint32_t T;       // index of the last entry that differs from its successor (offs[T] = total words)
-  uint32_t base;    // tile whose offset lane 0 holds
-  uint32_t window;  // this lane's offset
-  int lane;
-
-  // The two halves of a reload; between them the caller may do work that does not need the offsets.
-  __device__ __forceinline__ void request(uint32_t t) {
-    base = t;
-    const uint32_t idx = t + (uint32_t)lane;
-    window = offs[idx < T ? idx : T];
-  }
-  __device__ __forceinline__ void arrive() {
-    // Wait for the value here, inside the (rare) reload path: if its arrival were first needed
-    // after the paths join, every tile would pay a full "wait for all loads".
-    asm volatile("" : "+v"(window));
-  }
-  __device__ __forceinline__ void load(uint32_t t) {
-    request(t);
-    arrive();
-  }
-  // offsets of tiles t and t + 1 (reloads the window when t + 1 falls outside it)
-  __device__ __forceinline__ void get(uint32_t t, uint32_t& begin, uint32_t& end) {
-    if (t + 1 - base > 63u) load(t);
-    begin = (uint32_t)__builtin_amdgcn_readlane((int)window, (int)(t - base));
-    end = (uint32_t)__builtin_amdgcn_readlane((int)window, (int)(t + 1 - base));
-  }
-};
-
-// Words of a tile beyond the R*256 that the register ring stages (a tile denser than the kernel
-// variant was picked for): loaded and extracted on the spot.  Slow, rare, and out of line.
-__device__ __noinline__ void extract_overflow(const uint32_t* words, uint32_t begin, uint32_t end, unsigned char* tile) {
-  const int lane = threadIdx.x & 63;
-  for (uint32_t i = begin + lane * 4; i < end; i += 256) {
-    const u32x4 w = *(const u32x4*)(words + i);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) *(uint16_t*)(tile + ((w[j] & 0xffffu) << 1)) = (uint16_t)(w[j] >> 16);
-  }
-}
-
-// X in MFMA fragment order: block (K tile kt, column block nb) holds, for lane l = 16 g + c, the 8
-// halves X[32 kt + 8 g .. +7][16 nb + c] (zeros for columns past N).  One wave per block; loads are
-// quad-contiguous (lane j reads column j >> 2, chunk j & 3), stores go to the fragment position.
-__global__ __launch_bounds__(256) void xpack_kernel(const _Float16* X, _Float16* Xp, uint32_t K, uint32_t N, uint32_t units,
-                                                    uint32_t blocks) {
-  const uint32_t u = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (u >= units) return;
-  const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t kt = u / blocks, nb = u - kt * blocks;
-  const uint32_t c = lane >> 2, g = lane & 3u;
-  const uint32_t col = nb * 16u + c;
-  u32x4 v = {0u, 0u, 0u, 0u};
-  if (col < N) v = *(const u32x4*)(X + (size_t)col * K + kt * kTileK + g * 8u);
-  *(u32x4*)(Xp + ((size_t)u * 64u + g * 16u + c) * 8u) = v;
-}
-
-// WIDE: the variant for more than 32 columns - four waves per workgroup (one per SIMD, each with
-// the whole register file), X read from its repacked copy, tiles software-pipelined inside a wave.
-template <int NB, int WAVES, int R, int NS, bool WIDE>
+template <int NB, int WAVES, int R, int NS>
 __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   extern __shared__ __align__(16) unsigned char lds[];
   const int lane = threadIdx.x & 63;
@@ -108,7 +46,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   const uint32_t T = p.out.T, KT = p.out.KT;
   const uint32_t t0 = (uint32_t)((uint64_t)g * T / G), t1 = (uint32_t)((uint64_t)(g + 1) * T / G);
   const uint32_t share0 = share_begin(blockIdx.x, T, gridDim.x), share1 = share_begin(blockIdx.x + 1, T, gridDim.x);
-  constexpr int kWaveLds = wave_lds(NB, WIDE);
+  constexpr int kWaveLds = wave_lds(NB);
   // the first offsets are on their way while LDS is set up
   OffsetWindow win;
   win.offs = p.offs;
@@ -133,7 +71,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[rb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
 
-  typename std::conditional<WIDE, XPacked, XFrags>::type xf;
+  XFrags xf;
   xf.init(p.X, p.K, p.out.N, p.out.n0, lane);
   win.arrive();
   const unsigned char* frag = tile + ((lane >> 4) * kTileM + (lane & 15)) * 16;
@@ -176,18 +114,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const uint32_t q = r * 64 + lane;
-      if constexpr (WIDE) {
-        // branch-free, so that the whole step is one basic block and the scheduler may spread the
-        // MFMAs of the previous tile between these stores: lanes past the end of the run (their
-        // loads returned 0) are pointed at the slot that padding words go to
-        const bool valid = q * 4 < n;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const uint32_t w = valid ? s[r][j] : (uint32_t)kTileElems;
-          if (FLS_ABLATE & 4) asm volatile("" ::"v"(w));
-          else *(uint16_t*)(tile + ((w & 0xffffu) << 1)) = (uint16_t)(w >> 16);
-        }
-      } else if (q * 4 < n) {
+      if (q * 4 < n) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const uint32_t w = s[r][j];
@@ -202,7 +129,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   // rst_smem for sparse tiles: instead of zeroing all 8 KB (eight 16 B stores per lane, 64 LDS
   // clocks), store a zero at the places the tile's words went to - the same count of 2 B stores
   // as the extraction, which is less LDS time as long as a tile has at most about 1000 words.
-  constexpr bool kUnscatter = !WIDE && R <= 4;
+  constexpr bool kUnscatter = R <= 4;
   auto unscatter = [&](const u32x4(&s)[R], uint32_t begin, uint32_t end) {
     const uint32_t n = end - begin;
     if (n > R * 256u) {  // the overflow path wrote words this wave no longer holds
@@ -242,10 +169,8 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   };
   auto compute = [&]() {
     half8 x[NB];
-    if constexpr (!WIDE) {
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) x[nb] = xf.frag(xs, nb);
-    }
+    for (int nb = 0; nb < NB; ++nb) x[nb] = xf.frag(xs, nb);
     // fragments of H row blocks at a time (all eight when the accumulators leave the registers for it)
     constexpr int H = NB == 1 ? 8 : (NB == 2 ? 4 : 2);
 #pragma unroll
@@ -314,7 +239,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
       else __builtin_amdgcn_s_setprio(0);
     }
     extract(ss, b, e);
-    if constexpr (!WIDE) xf.template stage<NB>(xs, sx);
+    xf.template stage<NB>(xs, sx);
     if constexpr (kUnscatter) {
       half8 fa[kRowBlocks], fb[NB];
       read_frags(fa);
@@ -331,34 +256,6 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     ++tc;
   };
 
-  // With one wave per SIMD (the wide variant) nothing else fills a wave's waits, so its tiles are
-  // software-pipelined: a step first reads the fragments of its tile, which the step before put
-  // into LDS, then extracts the NEXT tile behind those reads, and only then runs the MFMAs - the
-  // LDS latency of the fragment reads passes during the extraction, and the extraction's
-  // instructions issue in the shadow of the MFMAs.  `ss`, `sx` are the stage of the next tile; xb
-  // carries a tile's X fragments from the step that frees their stage to the step that uses them.
-  half8 xb[NB];
-  auto step_pipelined = [&](u32x4(&ss)[R], u32x4(&sx)[NB], uint32_t& b, uint32_t& e) {
-    half8 fa[kRowBlocks], fb[NB];
-    read_frags(fa);
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) fb[nb] = xb[nb];
-    extract(ss, b, e);  // empty past the end of the piece
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) xb[nb] = __builtin_bit_cast(half8, sx[nb]);
-    issue(ss, sx, b, e);
-    mfma(fa, fb);
-    // asks the scheduler for: one MFMA, then up to three instructions of the other kinds (VALU,
-    // SALU, memory, LDS), 8 * NB times over
-#pragma unroll
-    for (int i = 0; i < kRowBlocks * NB; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002 | 0x004 | 0x010 | 0x080, 3, 0);
-    }
-    if (tc == t0) FLS_STAMP(p.out.flags, 512 + blockIdx.x, wave);
-    ++tc;
-  };
-
   if (WAVES > 4 && wave >= WAVES / 2) __builtin_amdgcn_s_setprio(1);
   while (tc < t1) {
     const uint32_t piece0 = tc;
@@ -367,27 +264,13 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     kti = ktc;
 #pragma unroll
     for (int i = 0; i < NS; ++i) issue(s[i], x[i], sb[i], se[i]);
-    if constexpr (WIDE) {
-      extract(s[0], sb[0], se[0]);
+    while (tc + NS <= pend) {
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) xb[nb] = __builtin_bit_cast(half8, x[0][nb]);
-      issue(s[0], x[0], sb[0], se[0]);
-      while (tc + NS <= pend) {
-#pragma unroll
-        for (int i = 0; i < NS; ++i) step_pipelined(s[(i + 1) % NS], x[(i + 1) % NS], sb[(i + 1) % NS], se[(i + 1) % NS]);
-      }
-#pragma unroll
-      for (int i = 0; i < NS - 1; ++i)
-        if (tc < pend) step_pipelined(s[(i + 1) % NS], x[(i + 1) % NS], sb[(i + 1) % NS], se[(i + 1) % NS]);
-    } else {
-      while (tc + NS <= pend) {
-#pragma unroll
-        for (int i = 0; i < NS; ++i) step(s[i], x[i], sb[i], se[i]);
-      }
-#pragma unroll
-      for (int i = 0; i < NS - 1; ++i)
-        if (tc < pend) step(s[i], x[i], sb[i], se[i]);
+      for (int i = 0; i < NS; ++i) step(s[i], x[i], sb[i], se[i]);
     }
+#pragma unroll
+    for (int i = 0; i < NS - 1; ++i)
+      if (tc < pend) step(s[i], x[i], sb[i], se[i]);
     hand_over(bandc, pend - piece0);
     ktc += pend - piece0;
     if (ktc == KT) {
@@ -410,7 +293,6 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 // per tile) get a deeper ring, as far as the registers allow: a stage costs 4 R + 4 NB registers,
 // the accumulators 32 NB, and a wave has 256 registers with eight waves per workgroup, 512 with four.
 constexpr int ring_depth(int NB, int WAVES, int R) {
-  if (WAVES <= 4) return R <= 2 ? 8 : (R <= 4 ? 6 : (R <= 6 ? 4 : 3));
   if (NB == 1) return FLS_NSTAGE;
   return R <= 2 ? 4 : 2;
 }
@@ -418,16 +300,15 @@ constexpr int ring_depth(int NB, int WAVES, int R) {
 template <int NB, int WAVES, int R>
 static hipError_t launch_variant(const SpmmParams& p, int grid, hipStream_t stream) {
   constexpr int NS = ring_depth(NB, WAVES, R);
-  constexpr bool WIDE = WAVES <= 4;
   static bool attr_done = false;
-  const int lds_bytes = WAVES * wave_lds(NB, WIDE) + (int)sizeof(WgReduceLds<NB>);
+  const int lds_bytes = WAVES * wave_lds(NB) + (int)sizeof(WgReduceLds<NB>);
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)spmm_kernel<NB, WAVES, R, NS, WIDE>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    hipError_t e = hipFuncSetAttribute((const void*)spmm_kernel<NB, WAVES, R, NS>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        lds_bytes);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL((spmm_kernel<NB, WAVES, R, NS, WIDE>), dim3(grid), dim3(WAVES * 64), lds_bytes, stream, p);
+  hipLaunchKernelGGL((spmm_kernel<NB, WAVES, R, NS>), dim3(grid), dim3(WAVES * 64), lds_bytes, stream, p);
   return hipGetLastError();
 }
 
@@ -462,10 +343,7 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
   else if (a.max_tile_words <= 4 * 256) R = 4;
   else if (a.max_tile_words <= 6 * 256) R = 6;
   if (a.N > kGroupCols) {
-    // the wide variant reads X from a copy in MFMA fragment order, made once per call
-    const uint32_t blocks = (a.N + 15u) / 16u, units = p.out.KT * blocks;
-    hipLaunchKernelGGL(xpack_kernel, dim3((units + 3) / 4), dim3(256), 0, stream, a.X, a.xpack, a.K, a.N, units, blocks);
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch_xpack(a, stream);  // the 64-column passes read X from a copy in fragment order
     if (e != hipSuccess) return e;
   }
   uint32_t launches = 0;
@@ -483,8 +361,7 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
       e = launch_r<2, 8>(R, p, grid, stream);
       n0 += 32;
     } else {
-      p.X = a.xpack;
-      e = launch_r<4, 4>(R, p, grid, stream);
+      e = launch_spmm_wide(a, n0, stream);
       n0 += kSpmmGroupCols;
     }
     if (e != hipSuccess) return e;

@@ -1,0 +1,346 @@
+// fls_spmm for more than 32 columns: 64 columns per pass (Flash-LLM's kernel for its widest batch
+// sizes, re-cut for gfx950).
+//
+// With 64 columns a tile needs 4 KB of X against some 1.6 - 5 KB of compressed W, and a CU's
+// vector-memory path moves only a few tens of bytes per clock, so re-reading X from L2 for every
+// row band bounds the kernel long before HBM or the MFMAs do.  Here X goes through LDS instead and
+// is shared: a workgroup has four waves, each on its own row band (four consecutive bands, one
+// wave per SIMD with the whole register file: 128 accumulator registers and a deep load ring),
+// all four walking the same K range tile by tile.  Every wave fetches one of every four X tiles
+// and puts it into LDS for all of them (double-buffered chunks of four tiles, one workgroup
+// barrier per chunk), which cuts the X traffic of a CU by four.
+//
+// Work is cut as (group of four bands) x (K slice): S slices per group so that the grid fills
+// the CUs.  A wave's accumulators are its band's partial result for its slice: with S = 1 they are
+// stored to C directly, otherwise to a partial-sum area [band][slice] that a second, small kernel
+// adds up in slice order and converts (no flags, no waiting between workgroups).
+//
+// Inside a wave the stages are those of the narrow kernel - register ring of tiles, extraction by
+// 2 B LDS stores, 16 B fragment reads, v_mfma_f32_16x16x32_f16 - software-pipelined, since no
+// second wave shares the SIMD: a step reads the fragments of its tile, extracts the next tile
+// behind those reads, and runs its MFMAs spread between the extraction's instructions.
+#include "fls_device.h"
+#include "fls_launch.h"
+#include "fls_tile.h"
+
+namespace fls {
+
+constexpr int kWideWaves = 4;                   // = bands per group = X tiles per chunk
+constexpr int kWideNB = 4;                      // column blocks per pass
+constexpr int kWideTileLds = kTileBytes + 16;   // a wave's tile + the slot padding words land in
+constexpr int kXTileBytes = kWideNB * 1024;     // one K tile of X for 64 columns, in fragment order
+constexpr int kXChunkBytes = kWideWaves * kXTileBytes;
+constexpr int kWideLdsBytes = kWideWaves * kWideTileLds + 2 * kXChunkBytes;
+
+struct WideParams {
+  const uint32_t* offs;   // TileOffsets
+  const uint32_t* words;  // NonZeros
+  const _Float16* Xp;     // X in fragment order: [K tile][column block of all N][lane][8 halves]
+  _Float16* C;
+  float* parts;           // [band][slice][column block][row block][lane] float4, used when S > 1
+  uint32_t M, N, n0, KT, bands, S;
+};
+
+// X in MFMA fragment order: block (K tile kt, column block nb) holds, for lane l = 16 g + c, the 8
+// halves X[32 kt + 8 g .. +7][16 nb + c] (zeros for columns past N).  One wave per block; loads are
+// quad-contiguous (lane j reads column j >> 2, chunk j & 3), stores go to the fragment position.
+__global__ __launch_bounds__(256) void xpack_kernel(const _Float16* X, _Float16* Xp, uint32_t K, uint32_t N, uint32_t units,
+                                                    uint32_t blocks) {
+  const uint32_t u = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (u >= units) return;
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t kt = u / blocks, nb = u - kt * blocks;
+  const uint32_t c = lane >> 2, g = lane & 3u;
+  const uint32_t col = nb * 16u + c;
+  u32x4 v = {0u, 0u, 0u, 0u};
+  if (col < N) v = *(const u32x4*)(X + (size_t)col * K + kt * kTileK + g * 8u);
+  *(u32x4*)(Xp + ((size_t)u * 64u + g * 16u + c) * 8u) = v;
+}
+
+template <int R, int NS>
+__global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p) {
+  constexpr int NB = kWideNB;
+  static_assert(NS % kWideWaves == 0, "the unrolled ring must hold whole X chunks");
+  extern __shared__ __align__(16) unsigned char lds[];
+  const int lane = threadIdx.x & 63;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t group = blockIdx.x / p.S, slice = blockIdx.x - group * p.S;
+  const uint32_t band = group * kWideWaves + wave;
+  const uint32_t KT = p.KT, T = p.bands * KT;
+  const uint32_t k0 = (uint32_t)((uint64_t)slice * KT / p.S), k1 = (uint32_t)((uint64_t)(slice + 1) * KT / p.S);
+  // a wave past the last band walks an empty run: it still fetches its share of X and meets the barriers
+  const bool active = band < p.bands;
+  const uint32_t t0 = active ? band * KT + k0 : T, t1 = active ? band * KT + k1 : T;
+  // bodies of NS steps; every wave of the workgroup runs the same number of them
+  const uint32_t bodies = (k1 - k0 + NS - 1) / NS;
+
+  unsigned char* tile = lds + wave * kWideTileLds;
+  unsigned char* xbuf = lds + kWideWaves * kWideTileLds;
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
+
+  float4v acc[kRowBlocks][NB];
+#pragma unroll
+  for (int rb = 0; rb < kRowBlocks; ++rb)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[rb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
+
+  // X: tile kt holds blocks of all columns of the call; this pass takes four from block n0 / 16 on.
+  const uint32_t xblocks = (p.N + 15u) / 16u;
+  const __amdgpu_buffer_rsrc_t xrsrc =
+      __builtin_amdgcn_make_buffer_rsrc((void*)p.Xp, 0, (int)(KT * xblocks * 1024u), kBufferFlags);
+  const uint32_t xlane = (p.n0 / 16u) * 1024u + (uint32_t)lane * 16u;
+  // the last pass of a call may have fewer than four column blocks left: the others read as zero
+  const uint32_t xvalid = xblocks - p.n0 / 16u;
+  // (everything that may leave the buffer is in the per-lane offset: that is the part the
+  // bounds check of a raw buffer looks at)
+  auto xload = [&](u32x4(&xr)[NB], uint32_t chunk) {
+    const uint32_t kt = k0 + chunk * kWideWaves + wave;
+    // tiles past the slice (the padding of the last body) must contribute nothing even if X holds
+    // Inf or NaN further along K: their X reads as zero
+    const uint32_t base = kt * xblocks * 1024u + xlane;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const bool wanted = kt < k1 && (uint32_t)nb < xvalid;
+      xr[nb] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, wanted ? base + nb * 1024u : 0xffffff00u, 0, 0);  // else: 0
+    }
+  };
+  auto xstore = [&](const u32x4(&xr)[NB], uint32_t buf) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) *(u32x4*)(xbuf + buf * kXChunkBytes + wave * kXTileBytes + nb * 1024 + lane * 16) = xr[nb];
+  };
+
+  // TileOffsets: a window of 64 entries in a VGPR (lane i = entry base + i), replaced once per
+  // body by the window that was requested a body earlier - an unconditional load per NS tiles, so
+  // stepping from tile to tile costs v_readlane and no wait.
+  const uint32_t* offs = p.offs;
+  auto window_at = [&](uint32_t first) {
+    const uint32_t idx = first + (uint32_t)lane;
+    return offs[idx < T ? idx : T];
+  };
+  uint32_t wbase = t0, window = window_at(t0);
+  uint32_t ti = t0;  // next tile to request
+  auto issue = [&](u32x4(&s)[R], uint32_t& begin, uint32_t& end) {
+    begin = (uint32_t)__builtin_amdgcn_readlane((int)window, (int)(ti - wbase));
+    end = (uint32_t)__builtin_amdgcn_readlane((int)window, (int)(ti + 1 - wbase));
+    uint32_t n = end - begin;
+    if (n > R * 256u) n = R * 256u;
+    if (ti >= t1) {  // past the run: nothing to load, nothing to extract
+      n = 0;
+      end = begin;
+    }
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(p.words + begin), 0, (int)(n * 4u), kBufferFlags);
+#pragma unroll
+    for (int r = 0; r < R; ++r) s[r] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (r * 64 + lane) * 16, 0, kAuxNonTemporal);
+    ++ti;
+  };
+
+  // extract (Alg. 2), branch-free so that a step is one basic block: lanes past the end of the
+  // run (their loads returned 0) are pointed at the slot that padding words go to
+  auto extract = [&](const u32x4(&s)[R], uint32_t begin, uint32_t end) {
+    const uint32_t n = end - begin;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const bool valid = (r * 64 + lane) * 4u < n;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t w = valid ? s[r][j] : (uint32_t)kTileElems;
+        *(uint16_t*)(tile + ((w & 0xffffu) << 1)) = (uint16_t)(w >> 16);
+      }
+    }
+    if (n > R * 256u) extract_overflow(p.words, begin + R * 256u, end, tile);
+  };
+
+  const unsigned char* frag = tile + ((lane >> 4) * kTileM + (lane & 15)) * 16;
+  u32x4 s[NS][R];
+  uint32_t sb[NS], se[NS];
+  u32x4 xr[NB];
+
+  // rst_smem.  Sparse tiles (R <= 4: at most 1024 words) are re-zeroed by storing zeros where
+  // their words went - as many 2 B stores as the extraction - instead of clearing all 8 KB.
+  constexpr bool kUnscatter = R <= 4;
+  auto unscatter = [&](const u32x4(&s)[R], uint32_t begin, uint32_t end) {
+    const uint32_t n = end - begin;
+    if (n > R * 256u) {  // the overflow path wrote words this wave no longer holds (never, if the header is honest)
+#pragma unroll
+      for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const bool valid = (r * 64 + lane) * 4u < n;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t w = valid ? s[r][j] : (uint32_t)kTileElems;
+        *(uint16_t*)(tile + ((w & 0xffffu) << 1)) = (uint16_t)0;
+      }
+    }
+  };
+
+  // One tile, whose words stage `cur` still holds and which the step before extracted into LDS:
+  // its fragments are read (A from the wave's tile, B from the X chunk), the tile is re-zeroed
+  // behind the reads, stage `cur` is refilled, the next tile (stage `nxt`) is extracted, and the
+  // MFMAs run spread between those instructions.
+  auto step = [&](u32x4(&cur)[R], uint32_t& cb, uint32_t& ce, const u32x4(&nxt)[R], uint32_t nb_, uint32_t ne_,
+                  const unsigned char* xt) {
+    half8 fa[kRowBlocks], fb[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) fb[nb] = *(const half8*)(xt + nb * 1024 + lane * 16);
+#pragma unroll
+    for (int j = 0; j < kRowBlocks; ++j) fa[j] = *(const half8*)(frag + j * 256);
+    if constexpr (kUnscatter) {
+      unscatter(cur, cb, ce);
+    } else {
+#pragma unroll
+      for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
+    }
+    issue(cur, cb, ce);
+    extract(nxt, nb_, ne_);
+#pragma unroll
+    for (int j = 0; j < kRowBlocks; ++j)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+        acc[j][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[j], fb[nb], acc[j][nb], 0, 0, 0);
+    // asks the scheduler for: one MFMA, then up to three instructions of the other kinds
+#pragma unroll
+    for (int i = 0; i < kRowBlocks * NB; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002 | 0x004 | 0x010 | 0x080, 3, 0);
+    }
+  };
+
+  // prologue: ring filled, first tile in LDS, first X chunk in LDS
+  xload(xr, 0);
+#pragma unroll
+  for (int i = 0; i < NS; ++i) issue(s[i], sb[i], se[i]);
+  uint32_t next_window = window_at(t0 + NS);
+  extract(s[0], sb[0], se[0]);
+  xstore(xr, 0);
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+
+  constexpr int kChunksPerBody = NS / kWideWaves;
+  for (uint32_t body = 0; body < bodies; ++body) {
+    // refills of this body ask for tiles t0 + NS * body + NS ... + 2 NS - 1: inside the window
+    // that starts at t0 + NS * (body + 1)
+    window = next_window;
+    wbase = t0 + NS * (body + 1);
+    next_window = window_at(t0 + NS * (body + 2));
+#pragma unroll
+    for (int c = 0; c < kChunksPerBody; ++c) {
+      const uint32_t chunk = body * kChunksPerBody + c;
+      xload(xr, chunk + 1);
+#pragma unroll
+      for (int j = 0; j < kWideWaves; ++j) {
+        const int i = c * kWideWaves + j, i1 = (i + 1) % NS;  // stages of this tile and of the next
+        step(s[i], sb[i], se[i], s[i1], sb[i1], se[i1], xbuf + (chunk & 1u) * kXChunkBytes + j * kXTileBytes);
+      }
+      xstore(xr, (chunk + 1) & 1u);
+      // the chunk just written is complete, and nobody still reads the one written next
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    }
+  }
+
+  if (!active) return;
+  if (p.S == 1) {
+    OutParams o;
+    o.C = p.C;
+    o.M = p.M;
+    o.N = p.N;
+    o.n0 = p.n0;
+    store_band<NB>(o, acc, band, lane);
+  } else {
+    float4v* dst = (float4v*)p.parts + ((size_t)(band * p.S + slice) * (NB * kRowBlocks)) * 64 + lane;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int rb = 0; rb < kRowBlocks; ++rb) dst[(nb * kRowBlocks + rb) * 64] = acc[rb][nb];
+  }
+}
+
+// Adds the S partial results of every band in slice order, converts, writes C.  One wave per
+// (band, column block, row block): S loads of 16 B per lane, all issued before the first is used.
+__global__ __launch_bounds__(256) void wide_reduce_kernel(WideParams p) {
+  const uint32_t unit = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (unit >= p.bands * (kWideNB * kRowBlocks)) return;
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t band = unit / (kWideNB * kRowBlocks), sub = unit - band * (kWideNB * kRowBlocks);
+  const uint32_t nb = sub / kRowBlocks, rb = sub - nb * kRowBlocks;
+  const float4v* src = (const float4v*)p.parts + ((size_t)band * p.S * (kWideNB * kRowBlocks) + sub) * 64 + lane;
+  float4v sum = {0.f, 0.f, 0.f, 0.f};
+  for (uint32_t s0 = 0; s0 < p.S; s0 += 8) {
+    float4v v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t s = s0 + j < p.S ? s0 + j : s0;
+      v[j] = src[(size_t)s * (kWideNB * kRowBlocks) * 64];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (s0 + j < p.S) sum += v[j];
+  }
+  const uint32_t n = p.n0 + nb * 16 + (lane & 15u);
+  if (n < p.N) {
+    half4 h;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) h[r] = (_Float16)sum[r];
+    *(half4*)(p.C + (size_t)n * p.M + band * kTileM + rb * 16 + (lane >> 4) * 4) = h;
+  }
+}
+
+template <int R, int NS>
+static hipError_t launch_wide_variant(const WideParams& p, int grid, hipStream_t stream) {
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)spmm_wide_kernel<R, NS>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       kWideLdsBytes);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL((spmm_wide_kernel<R, NS>), dim3(grid), dim3(kWideWaves * 64), kWideLdsBytes, stream, p);
+  return hipGetLastError();
+}
+
+// X (all N columns of the call) into fragment order, once per call.
+hipError_t launch_xpack(const SpmmLaunch& a, hipStream_t stream) {
+  const uint32_t blocks = (a.N + 15u) / 16u, units = (a.K / kTileK) * blocks;
+  hipLaunchKernelGGL(xpack_kernel, dim3((units + 3) / 4), dim3(256), 0, stream, a.X, a.xpack, a.K, a.N, units, blocks);
+  return hipGetLastError();
+}
+
+// One 64-column pass starting at column n0; `xpack` holds all N columns in fragment order.
+hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, hipStream_t stream) {
+  WideParams p;
+  p.offs = a.offs;
+  p.words = a.words;
+  p.Xp = a.xpack;
+  p.C = a.C;
+  p.parts = a.parts;
+  p.M = a.M;
+  p.N = a.N;
+  p.n0 = n0;
+  p.KT = a.K / kTileK;
+  p.bands = a.M / kTileM;
+  const uint32_t groups = (p.bands + kWideWaves - 1) / kWideWaves;
+  p.S = wide_slices(p.bands, p.KT, a.num_cus);
+  const int grid = (int)(groups * p.S);
+  hipError_t e;
+  // rounds of 256 words staged per tile; the ring is 8 tiles deep while the registers allow
+  if (a.max_tile_words <= 2 * 256) e = launch_wide_variant<2, 8>(p, grid, stream);
+  else if (a.max_tile_words <= 4 * 256) e = launch_wide_variant<4, 8>(p, grid, stream);
+  else if (a.max_tile_words <= 6 * 256) e = launch_wide_variant<6, 4>(p, grid, stream);
+  else e = launch_wide_variant<8, 4>(p, grid, stream);
+  if (e != hipSuccess) return e;
+  if (p.S > 1) {
+    const uint32_t units = p.bands * (kWideNB * kRowBlocks);
+    hipLaunchKernelGGL(wide_reduce_kernel, dim3((units + 3) / 4), dim3(256), 0, stream, p);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+}  // namespace fls
