@@ -25,20 +25,23 @@ MIN_ROTATION_BYTES = 1 << 30
 MEASURED_TRAFFIC_BYTES = {"C2": 170.44e6}  # profiles/spmm_C2_hbm_traffic.md
 
 
-def _time_loop(fn, copies, steps, warmup):
+def _time_loop(calls, steps, warmup):
+    """calls: prepared zero-argument launches (one per rotated copy of the weights), issued round-robin.
+    Returns (GPU ms per step from events on the launch stream, host ms per step spent issuing)."""
     import torch
 
+    n = len(calls)
     for i in range(warmup):
-        fn(copies[i % len(copies)])
+        calls[i % n]()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
     e0.record()
+    t0 = time.perf_counter()
     for i in range(steps):
-        fn(copies[i % len(copies)])
+        calls[i % n]()
+    host_ms = (time.perf_counter() - t0) * 1e3
     e1.record()
     torch.cuda.synchronize()
-    host_ms = (time.perf_counter() - t0) * 1e3
     return e0.elapsed_time(e1) / steps, host_ms / steps
 
 
@@ -71,7 +74,7 @@ def run_sweep(args):
     dense_ms = {}
     for N in wl.SWEEP_NS:
         D = torch.empty((N, M), dtype=torch.float16, device="cuda")
-        dense_ms[N], _ = _time_loop(lambda w: fls.fls_dense_gemm(w, Xd[N], D, M, K, N), dense, args.steps, args.warmup)
+        dense_ms[N], _ = _time_loop([fls.prepare_dense_gemm(w, Xd[N], D, M, K, N) for w in dense], args.steps, args.warmup)
         emit({"point": f"dense-N{N}", "N": N, "us": round(dense_ms[N] * 1e3, 2),
               "GBps": round((2 * M * K + 2 * K * N + 2 * M * N) / dense_ms[N] / 1e6, 1)})
     del dense, Wd
@@ -87,7 +90,7 @@ def run_sweep(args):
             blobs = [blob0] + [blob0.clone() for _ in range(n_copies - 1)]
             for N in wl.SWEEP_NS:
                 C = torch.empty((N, M), dtype=torch.float16, device="cuda")
-                ms, _ = _time_loop(lambda b: fls.fls_spmm(b, Xd[N], C, M, K, N), blobs, args.steps, args.warmup)
+                ms, _ = _time_loop([fls.prepare_spmm(b, Xd[N], C, M, K, N) for b in blobs], args.steps, args.warmup)
                 ref = oracle.ref_spmm_f64(Wb, Xs[N], rows=(0, rows))
                 got = C.cpu().numpy()[:, :rows].astype(np.float64)
                 err = float(np.abs(got - ref[:, :rows]).max() / np.abs(ref[:, :rows]).max())
@@ -103,8 +106,9 @@ def run_sweep(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    # a step is ~40 us: the defaults keep the GPU busy long enough (tens of ms) for its clocks to settle
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--config", default="C2", help="C1..C4 (C2 is the configuration the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
@@ -145,7 +149,7 @@ def main():
     fls.ensure_workspace(M, K, N)
     C = torch.empty((N, M), dtype=torch.float16, device="cuda")
 
-    ms, host_ms = _time_loop(lambda b: fls.fls_spmm(b, X, C, M, K, N), blobs, args.steps, args.warmup)
+    ms, host_ms = _time_loop([fls.prepare_spmm(b, X, C, M, K, N) for b in blobs], args.steps, args.warmup)
     flops = 2.0 * M * K * N
     alg_bytes = st["bytes_total"] + 2 * K * N + 2 * M * N  # blob + X + C
     tflops = flops / (ms * 1e-3) / 1e12
@@ -182,7 +186,7 @@ def main():
         n_d = max(2, -(-MIN_ROTATION_BYTES // (2 * M * K)))
         dense = [Wd] + [Wd.clone() for _ in range(n_d - 1)]
         D = torch.empty((N, M), dtype=torch.float16, device="cuda")
-        dms, _ = _time_loop(lambda w: fls.fls_dense_gemm(w, X, D, M, K, N), dense, args.steps, args.warmup)
+        dms, _ = _time_loop([fls.prepare_dense_gemm(w, X, D, M, K, N) for w in dense], args.steps, args.warmup)
         dbytes = 2 * M * K + 2 * K * N + 2 * M * N
         out["dense_gemm"] = {"ms_per_step": round(dms, 5), "TFLOPs": round(flops / (dms * 1e-3) / 1e12, 2),
                              "achieved_GBps": round(dbytes / (dms * 1e-3) / 1e9, 1),

@@ -153,6 +153,48 @@ def fls_spmm(blob, X, C, M, K, N):
     return C
 
 
+def prepare_spmm(blob, X, C, M, K, N):
+    """Checks and marshals the arguments of fls_spmm once; returns a callable that enqueues the call on the stream
+    that was current when it was prepared.  For tight loops: a Python-side check per call costs as much time as
+    the kernel runs."""
+    import torch
+
+    assert blob.is_cuda and blob.dtype == torch.uint8 and blob.is_contiguous()
+    assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and tuple(X.shape) == (N, K)
+    assert C.is_cuda and C.dtype == torch.float16 and C.is_contiguous() and tuple(C.shape) == (N, M)
+    f = lib().fls_spmm
+    args = (ctypes.c_void_p(blob.data_ptr()), ctypes.c_void_p(X.data_ptr()), ctypes.c_void_p(C.data_ptr()),
+            M, K, N, _stream())
+    keep = (blob, X, C)  # the tensors stay alive as long as the callable does
+
+    def call(_keep=keep):
+        rc = f(*args)
+        if rc != OK:
+            _check(rc, "fls_spmm")
+
+    return call
+
+
+def prepare_dense_gemm(W, X, C, M, K, N):
+    """As prepare_spmm, for fls_dense_gemm."""
+    import torch
+
+    assert W.is_cuda and W.dtype == torch.float16 and W.is_contiguous() and tuple(W.shape) == (M, K)
+    assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and tuple(X.shape) == (N, K)
+    assert C.is_cuda and C.dtype == torch.float16 and C.is_contiguous() and tuple(C.shape) == (N, M)
+    f = lib().fls_dense_gemm
+    args = (ctypes.c_void_p(W.data_ptr()), ctypes.c_void_p(X.data_ptr()), ctypes.c_void_p(C.data_ptr()),
+            M, K, N, _stream())
+    keep = (W, X, C)
+
+    def call(_keep=keep):
+        rc = f(*args)
+        if rc != OK:
+            _check(rc, "fls_dense_gemm")
+
+    return call
+
+
 def fls_forget(blob=None):
     lib().fls_forget(ctypes.c_void_p(blob.data_ptr()) if blob is not None else None)
 

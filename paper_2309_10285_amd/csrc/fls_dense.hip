@@ -160,7 +160,7 @@ hipError_t launch_dense(const DenseLaunch& a, hipStream_t stream) {
   p.out.flags = a.flags;
   p.out.M = a.M;
   p.out.N = a.N;
-  const int grid = pick_grid(a.M / kTileM, a.num_cus);
+  const int grid = pick_grid(a.M / kTileM, a.K / kTileK, a.num_cus);
   for (uint32_t n0 = 0; n0 < a.N; n0 += kGroupCols) {
     p.out.n0 = n0;
     p.out.epoch = a.epoch0 + n0 / kGroupCols;

@@ -76,8 +76,13 @@ inline size_t xpack_bytes(uint32_t K, uint32_t N) {
 // of the kernel (store, count, read back: a few microseconds with the whole chip waiting) goes
 // away.  That is worth leaving up to a fifth of the CUs without a workgroup: the kernel is paced by
 // HBM, not by the CUs.  Otherwise every CU gets an equal share, cut wherever it falls.
-inline int pick_grid(uint32_t bands, int cus) {
+// A workgroup should also have enough tiles to amortise its start and its hand-over: small
+// problems get fewer workgroups (at least kMinShare tiles each).
+constexpr uint32_t kMinShare = 32;
+inline int pick_grid(uint32_t bands, uint32_t tiles_per_band, int cus) {
   if (cus > (int)kMaxWorkgroups) cus = (int)kMaxWorkgroups;
+  const uint64_t by_size = (uint64_t)bands * tiles_per_band / kMinShare;
+  if (by_size < (uint64_t)cus) cus = by_size > 0 ? (int)by_size : 1;
   if ((int)bands <= cus) {
     const int aligned = (int)bands * (cus / (int)bands);
     if (aligned * 5 >= cus * 4) return aligned;

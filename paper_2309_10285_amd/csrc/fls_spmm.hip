@@ -256,6 +256,31 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     ++tc;
   };
 
+  // When the workgroup's share is exactly one band (and one column block wide), every wave has
+  // one piece, all of the same band, and the sum needs no turns and no lock: each wave leaves
+  // its accumulators in its own tile buffer (8 KB, free once its run is over) and counts itself
+  // in; the wave that arrives last adds the others' up in wave order and writes C.  This is the
+  // common case of the band-aligned grid, and the last thing the whole chip waits for.
+  const bool band_aligned = NB == 1 && share0 % KT == 0 && share1 - share0 == KT && KT >= (uint32_t)WAVES;
+  auto whole_band_sum = [&](uint32_t band) {
+    if (tc == t1) FLS_STAMP(p.out.flags, 256 + blockIdx.x, wave);
+#pragma unroll
+    for (int rb = 0; rb < kRowBlocks; ++rb) *(float4v*)(tile + rb * 1024 + lane * 16) = acc[rb][0];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    uint32_t arrived = 0;
+    if (lane == 0) arrived = __hip_atomic_fetch_add(&red->cnt[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if (__builtin_amdgcn_readfirstlane(arrived) != (uint32_t)WAVES - 1) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    float4v sum[kRowBlocks][NB];
+#pragma unroll
+    for (int rb = 0; rb < kRowBlocks; ++rb) sum[rb][0] = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w)
+#pragma unroll
+      for (int rb = 0; rb < kRowBlocks; ++rb) sum[rb][0] += *(const float4v*)(lds + w * kWaveLds + rb * 1024 + lane * 16);
+    store_band<NB>(p.out, sum, band, lane);
+  };
+
   if (WAVES > 4 && wave >= WAVES / 2) __builtin_amdgcn_s_setprio(1);
   while (tc < t1) {
     const uint32_t piece0 = tc;
@@ -271,7 +296,8 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 #pragma unroll
     for (int i = 0; i < NS - 1; ++i)
       if (tc < pend) step(s[i], x[i], sb[i], se[i]);
-    hand_over(bandc, pend - piece0);
+    if (band_aligned) whole_band_sum(bandc);
+    else hand_over(bandc, pend - piece0);
     ktc += pend - piece0;
     if (ktc == KT) {
       ktc = 0;
@@ -335,7 +361,7 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
   p.out.M = a.M;
   p.out.N = a.N;
   p.out.KT = a.K / kTileK;
-  const int grid = pick_grid(a.M / kTileM, a.num_cus);
+  const int grid = pick_grid(a.M / kTileM, a.K / kTileK, a.num_cus);
   // rounds of 256 words staged per tile: the smallest variant that holds the densest tile
   // (a denser tile is still handled, through a slow path)
   int R = 8;
