@@ -87,7 +87,8 @@ int fls_compress_bound(int64_t M, int64_t K, size_t* bytes_host);
  * Dense masked W -> Tiled-CSL blob (the paper's offline weight reformatting step, Sec. 5, Alg. 3).
  *   W_dev        in : fp16 row-major M x K, pruned entries exactly +0 (0x0000)
  *   out_dev      out: blob; caller-owned, out_capacity bytes, 16-byte aligned
- *   order_policy in : FLS_ORDER_LOCATION or FLS_ORDER_BANK
+ *   order_policy in : FLS_ORDER_LOCATION (FLS_ORDER_BANK blobs are accepted by fls_spmm, but this
+ *                     call does not produce them: FLS_EINVAL)
  *   stats_host   out: may be NULL; filled on FLS_OK, and bytes_total also on FLS_ECAPACITY
  * The result is a pure function of (W bits, M, K, order_policy).  Waits for its own kernels.
  * Uses the start of out_dev as scratch, so out_capacity must cover header and TileOffsets even
@@ -101,22 +102,27 @@ int fls_compress(const void* W_dev, int64_t M, int64_t K, void* out_dev, size_t 
 int fls_inspect(const void* header_host, fls_stats* stats_host);
 
 /*
- * Bytes of device workspace fls_spmm / fls_dense_gemm need for this shape (split-K partial
- * sums and arrival counters; it grows with N only).  Returns 0 on invalid arguments.
+ * Bytes of device workspace fls_spmm / fls_dense_gemm need for this shape: a 4 MiB control area
+ * (per-workgroup flags of the split-K hand-over, an error word), the fp32 partial sums (2 - 4 MiB
+ * for N <= 32, 64 MiB for N > 32) and, for N > 32, K x N x 2 bytes for X repacked into MFMA
+ * fragment order.  Returns 0 on invalid arguments.
  */
 size_t fls_workspace_bytes(int64_t M, int64_t K, int64_t N);
 
 /*
  * Registers a caller-owned workspace (16-byte aligned) and clears it on `stream`.  The
- * workspace must stay valid, and untouched by the caller, until replaced.  Kernels leave it
- * clear when they finish, so one registration serves any number of calls; calls that share it
- * must not overlap in time.  Errors: FLS_EINVAL, FLS_EALIGN, FLS_EHIP.
+ * workspace must stay valid, and untouched by the caller, until replaced.  Nothing has to be
+ * cleared between calls (flags carry a per-launch number), so one registration serves any
+ * number of calls of any shape it is large enough for; calls that share it must not overlap
+ * in time.  Errors: FLS_EINVAL, FLS_EALIGN, FLS_EHIP.
  */
 int fls_set_workspace(void* ws_dev, size_t bytes, fls_stream_t stream);
 
 /*
- * C = W . X with W given as a Tiled-CSL blob (the SpMM of Alg. 1): streams the blob once from
- * HBM, rebuilds each tile densely in LDS, multiplies with MFMA, fp32 accumulation.
+ * C = W . X with W given as a Tiled-CSL blob (the SpMM of Alg. 1): streams the blob from HBM
+ * (once per 64 columns for N > 32, else once), rebuilds each tile densely in LDS, multiplies
+ * with MFMA, fp32 accumulation.  The result does not depend on timing: partial sums are added
+ * in a fixed order.  2*K*N and 2*M*N must stay below 2^31 (32-bit byte offsets into X and C).
  *   Wc_dev in : blob made by fls_compress (or byte-identical); its header must match M, K
  *   X_dev  in : fp16 column-major K x N;  C_dev out: fp16 column-major M x N (fully overwritten)
  * The first call on a given blob address reads its 64-byte header back (a blocking copy) to
