@@ -109,7 +109,7 @@ def main():
     # a step is ~40 us: the defaults keep the GPU busy long enough (tens of ms) for its clocks to settle
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--config", default="C2", help="C1..C4 (C2 is the configuration the metric is quoted on)")
+    ap.add_argument("--config", default="C2", help="C1..C4 (C2 is the configuration the metric is quoted on), L1, L2 (OPT-175B-sized)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--sweep", action="store_true",

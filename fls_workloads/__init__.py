@@ -96,6 +96,10 @@ CONFIGS = {
     "C2": Config("C2", 28672, 7168, 16, 0.80, "magnitude", 0x5EED0002, "OPT-30B-shaped FFN up-projection"),
     "C3": Config("C3", 27648, 9216, 32, 0.70, "magnitude", 0x5EED0003, "OPT-66B-shaped fused QKV"),
     "C4": Config("C4", 12288, 49152, 64, 0.90, "magnitude", 0x5EED0004, "OPT-175B-shaped FFN down-projection"),
+    # beyond the five named configurations: the largest MatMul of the paper's kernel benchmark (Sec. 6.1), where a
+    # call is long enough for the fixed cost of a launch not to matter
+    "L1": Config("L1", 49152, 12288, 16, 0.80, "magnitude", 0x5EED0006, "OPT-175B-shaped FFN up-projection"),
+    "L2": Config("L2", 49152, 12288, 8, 0.70, "magnitude", 0x5EED0007, "OPT-175B-shaped FFN up-projection"),
 }
 
 SWEEP_M = 12288
