@@ -3,7 +3,9 @@
 One "step" = one fls_spmm call over the OPT-30B-shaped FFN up-projection (W 28672 x 7168 fp16,
 magnitude-pruned to 80 %, X 7168 x 16), inputs resident in HBM.  Steps rotate over several
 copies of the compressed matrix so that no step finds its weights in the 256 MB Infinity Cache.
-Prints ONE JSON line (see the design doc for every field).
+Prints ONE JSON line: metric/value (dense-equivalent TFLOP/s), the roofline object of the SpMM kernel (algorithmic
+bytes per launch / measured launch time against the 8 TB/s HBM peak, measured HBM traffic), the own dense GEMM on the
+unpruned matrix, the CPU oracle timed on the host cores, and the parity of C against that oracle.
 """
 import argparse
 import json

@@ -102,6 +102,19 @@ int check_mm_args(const void* W, const void* X, void* C, int64_t M, int64_t K, i
 // every shape, so partial sums of one call can never be read as flags by the next.
 constexpr size_t kCounterAreaBytes = (size_t)4 << 20;
 uint32_t g_epoch = 0;  // launches since the workspace was registered; a flag equal to it is current
+
+// Reserves `count` launch numbers (call with g_mu held).  Before the 32-bit counter could wrap,
+// the control area is cleared again on the call's stream and the count restarts, so that a launch
+// number is never 0 and never meets a flag left by the launch 2^32 numbers earlier.
+int reserve_epochs(uint32_t count, hipStream_t stream, uint32_t* first) {
+  if (g_epoch > 0xffff0000u) {
+    if (fls::launch_fill_zero(g_ws, kCounterAreaBytes, stream) != hipSuccess) return FLS_EHIP;
+    g_epoch = 0;
+  }
+  *first = g_epoch + 1;
+  g_epoch += count;
+  return FLS_OK;
+}
 // then, for N > 32, X repacked into MFMA fragment order (K x N rounded up to 16 columns, fp16).
 void workspace_layout(int64_t K, int64_t N, size_t* total, size_t* xpack_offset) {
   const size_t parts = fls::parts_floats((uint32_t)N) * sizeof(float);
@@ -209,8 +222,8 @@ int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int6
     std::lock_guard<std::mutex> lk(g_mu);
     if (!g_ws || g_ws_bytes < need) return FLS_EWORKSPACE;
     ws = g_ws;
-    epoch0 = g_epoch + 1;  // one launch per column group
-    g_epoch += fls::column_groups((uint32_t)N);
+    rc = reserve_epochs(fls::column_groups((uint32_t)N), (hipStream_t)stream, &epoch0);  // one launch per column group at most
+    if (rc != FLS_OK) return rc;
     auto it = g_blobs.find(Wc_dev);
     known = it != g_blobs.end();
     if (known) info = it->second;
@@ -259,8 +272,8 @@ int fls_dense_gemm(const void* W_dev, const void* X_dev, void* C_dev, int64_t M,
     std::lock_guard<std::mutex> lk(g_mu);
     if (!g_ws || g_ws_bytes < need) return FLS_EWORKSPACE;
     ws = g_ws;
-    epoch0 = g_epoch + 1;
-    g_epoch += fls::column_groups((uint32_t)N);
+    rc = reserve_epochs(fls::column_groups((uint32_t)N), (hipStream_t)stream, &epoch0);
+    if (rc != FLS_OK) return rc;
   }
   const int cus = num_cus();
   if (cus <= 0) return FLS_EHIP;
