@@ -296,3 +296,18 @@ def test_back_to_back_shapes_share_one_workspace(fls, oracle_mod):
             assert _rel_err(D.cpu().numpy(), ref) <= TOL
     assert fls._ws_tensor is ws  # still the same registration
     assert int(ws[512 * 4:512 * 4 + 4].cpu().numpy().view(np.uint32)[0]) == 0  # error word: flags[512]
+
+
+def test_very_long_k(fls, oracle_mod):
+    """One row band with K = 2^21 (65536 K tiles, every workgroup inside the same band, byte offsets into X beyond
+    2^27): the blob against the oracle's, C for a narrow and a 64-column call."""
+    M, K = 128, 1 << 21
+    W = wl.prune_uniform(wl.gen_weights_f32(M, K, 31), 0.95, 32)
+    ref_blob = oracle_mod.ref_compress(W)
+    for N in (8, 64):
+        X = wl.gen_x(N, K, 33 + N)
+        blob, st, C = _run_spmm(fls, W, X, N)
+        if N == 8:
+            assert np.array_equal(blob.cpu().numpy(), ref_blob)
+        assert _rel_err(C, oracle_mod.ref_spmm_f64(W, X)) <= TOL
+    assert _rel_err(_run_dense(fls, W, X[:16], 16), oracle_mod.ref_spmm_f64(W, X[:16])) <= TOL
