@@ -108,8 +108,12 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     if (++kti == KT) kti = 0;
   };
 
-  // extract (Alg. 2): value = high half of the word, byte address = 2 * location
-  auto extract = [&](const u32x4(&s)[R], uint32_t begin, uint32_t end) {
+  // extract (Alg. 2): value = high half of the word, byte address = 2 * location.  Where the tile
+  // is re-zeroed by un-scatter, a word is replaced by the LDS address it went to, which is all
+  // that step needs.
+  typedef __attribute__((address_space(3))) uint16_t* lds_u16_ptr;
+  const uint32_t tile_addr = (uint32_t)(uintptr_t)tile;  // LDS addresses are the low 32 bits
+  auto extract = [&](u32x4(&s)[R], uint32_t begin, uint32_t end) {
     const uint32_t n = end - begin;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -118,8 +122,10 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const uint32_t w = s[r][j];
+          const uint32_t addr = tile_addr + ((w & 0xffffu) << 1);
           if (FLS_ABLATE & 4) asm volatile("" ::"v"(w));
-          else *(uint16_t*)(tile + ((w & 0xffffu) << 1)) = (uint16_t)(w >> 16);
+          else *(lds_u16_ptr)(uintptr_t)addr = (uint16_t)(w >> 16);
+          s[r][j] = addr;
         }
       }
     }
@@ -141,7 +147,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
         const uint32_t q = r * 64 + lane;
         if (q * 4 < n) {
 #pragma unroll
-          for (int j = 0; j < 4; ++j) *(uint16_t*)(tile + ((s[r][j] & 0xffffu) << 1)) = (uint16_t)0;
+          for (int j = 0; j < 4; ++j) *(lds_u16_ptr)(uintptr_t)s[r][j] = (uint16_t)0;
         }
       }
     }
