@@ -86,10 +86,10 @@ __device__ __forceinline__ void store_band(const OutParams& o, const float4v (&a
 // LDS area of the in-workgroup step: band slots and their control words.  A slot keeps a band's
 // running sum as [column block][row block][lane] float4.  Consecutive bands of a workgroup's
 // share alternate between two slots, so that waves already in the next band need not wait for
-// the previous one to be collected; with four column blocks a slot is 32 KB and there is one.
+// the previous one to be collected.
 template <int NB>
 struct WgReduceLds {
-  static constexpr uint32_t kSlots = NB <= 2 ? 2 : 1;
+  static constexpr uint32_t kSlots = 2;
   float4v slot[kSlots][NB * kRowBlocks * 64];
   uint32_t cnt[2];   // tiles added to the slot so far
   uint32_t gen[2];   // how many bands the slot has served
@@ -228,8 +228,8 @@ __device__ __forceinline__ void owner_finish(const OutParams& o, float4v (&acc)[
   FLS_STAMP(o.flags, wg, 6);
   // As many loads as the registers allow are issued before the first is used: each is a trip
   // to memory, and this runs when the kernel is about to end, with nothing left to hide it behind.
-  constexpr int kBatch = NB == 1 ? 4 : (NB == 2 ? 2 : 1);  // slots in flight
-  constexpr int kBlocks = NB == 4 ? 2 : NB;                 // column blocks of a slot in flight
+  constexpr int kBatch = NB == 1 ? 4 : 2;  // slots in flight
+  constexpr int kBlocks = NB;               // column blocks of a slot in flight
   uint32_t q = wg + 1;
   while (q < P && share_begin(q, o.T, P) < band_hi) {
     __amdgpu_buffer_rsrc_t src[kBatch];

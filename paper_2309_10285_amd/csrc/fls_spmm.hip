@@ -1,25 +1,30 @@
-// fls_spmm: Load-as-Sparse / Compute-as-Dense SpMM for gfx950 (Flash-LLM, Alg. 1 re-designed
-// for wave64 / MFMA / 160 KB LDS).
+// fls_spmm, passes of up to 32 columns: Load-as-Sparse / Compute-as-Dense SpMM for gfx950
+// (Flash-LLM, Alg. 1 re-designed for wave64 / MFMA / 160 KB LDS).
 //
-// One persistent workgroup per CU; every wave owns a contiguous run of Tiled-CSL tiles and a
-// private 8 KB LDS tile, so the stages of Alg. 1 run per wave with no workgroup barrier:
+// One persistent workgroup per CU; every wave owns a contiguous run of Tiled-CSL tiles, which it
+// walks piece by piece (a piece = its tiles of one row band), and a private 8 KB LDS tile, so the
+// stages of Alg. 1 run per wave with no workgroup barrier:
 //   gmem2reg : the tile's words stream from HBM into VGPRs with 16 B non-temporal loads,
 //              a few tiles ahead of their use (register ring)
 //   extract  : each word's fp16 value is stored at its location in the zero-filled LDS tile
 //              (Alg. 2); the location field already is the position in the MFMA operand layout
-//   smem2tc  : A fragments are 16 B LDS reads, B fragments (X) come straight from L2 as 16 B
-//              loads, v_mfma_f32_16x16x32_f16 accumulates in fp32
-//   rst_smem : the tile is zeroed again right after its fragments were read (LDS operations of a
-//              wave execute in order, so no wait separates the stages)
+//   smem2tc  : A fragments are 16 B LDS reads; B fragments (X) come from L2 as 16 B loads in the
+//              ring and pass through a 1 KB LDS stage that puts them into MFMA order;
+//              v_mfma_f32_16x16x32_f16 accumulates in fp32
+//   rst_smem : right behind the fragment reads (LDS operations of a wave execute in order, so no
+//              wait separates the stages) the tile is made zero again: sparse tiles by storing
+//              zeros where their words went, dense ones by clearing all 8 KB
 // Split-K: the tile sequence (band-major) is cut evenly over all waves of the grid; partial
 // bands are summed in LDS inside a workgroup and through fp32 slots in HBM between workgroups.
+// More than 32 columns: fls_spmm_wide.hip.
 #include "fls_device.h"
 #include "fls_launch.h"
 #include "fls_tile.h"
 
 // Latency-breakdown builds (the paper's Fig. 11 method: erase the other operations and time what is
 // left).  FLS_ABLATE is a bit mask, 0 in the library: 1 no split-K hand-over, 2 no MFMA, 4 no extract,
-// 8 no re-zeroing, 16 no LDS fragment reads, 32 no global loads of the words, 64 no hand-over between workgroups, 128 no reduction inside the workgroup.  Results are wrong by design.
+// 8 no re-zeroing, 16 no LDS fragment reads, 32 no global loads of the words, 64 no hand-over
+// between workgroups, 128 no reduction inside the workgroup.  Results are wrong by design.
 #ifndef FLS_ABLATE
 #define FLS_ABLATE 0
 #endif
@@ -32,7 +37,7 @@ constexpr int wave_lds(int NB) { return kTileBytes + 16 + NB * 1024; }
 struct SpmmParams {
   const uint32_t* offs;   // TileOffsets
   const uint32_t* words;  // NonZeros
-  const _Float16* X;      // X, or its repacked copy for the wide variant
+  const _Float16* X;
   uint32_t K;
   OutParams out;
 };
@@ -158,10 +163,6 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
       if (FLS_ABLATE & 16) a[j] = half8{1, 1, 1, 1, 1, 1, 1, 1};
       else a[j] = *(const half8*)(frag + j * 256);
     }
-    if (!kUnscatter && !(FLS_ABLATE & 8)) {
-#pragma unroll
-      for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
-    }
   };
   auto mfma = [&](const half8(&a)[kRowBlocks], const half8(&b)[NB]) {
 #pragma unroll
@@ -178,7 +179,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) x[nb] = xf.frag(xs, nb);
     // fragments of H row blocks at a time (all eight when the accumulators leave the registers for it)
-    constexpr int H = NB == 1 ? 8 : (NB == 2 ? 4 : 2);
+    constexpr int H = NB == 1 ? 8 : 4;
 #pragma unroll
     for (int h = 0; h < kRowBlocks; h += H) {
       half8 a[H];
