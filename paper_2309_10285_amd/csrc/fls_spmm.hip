@@ -263,13 +263,15 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     ++tc;
   };
 
-  // When the workgroup's share is exactly one band (and one column block wide), every wave has
-  // one piece, all of the same band, and the sum needs no turns and no lock: each wave leaves
-  // its accumulators in its own tile buffer (8 KB, free once its run is over) and counts itself
-  // in; the wave that arrives last adds the others' up in wave order and writes C.  This is the
-  // common case of the band-aligned grid, and the last thing the whole chip waits for.
-  const bool band_aligned = NB == 1 && share0 % KT == 0 && share1 - share0 == KT && KT >= (uint32_t)WAVES;
-  auto whole_band_sum = [&](uint32_t band) {
+  // When the workgroup's share lies inside one band (and is one column block wide, with a tile for
+  // every wave), every wave has one piece, all of the same band, and the sum needs no turns and
+  // no lock: each wave leaves its accumulators in its own tile buffer (8 KB, free once its run is
+  // over) and counts itself in; the wave that arrives last adds them up in wave order and does
+  // with the sum what the share's place in the band asks for - writes C (the whole band: the case
+  // of the band-aligned grid, and the last thing the whole chip waits for), keeps it as the
+  // band's owner, or stores it as the workgroup's partial sum.
+  const bool one_band = NB == 1 && share0 / KT == (share1 - 1) / KT && share1 - share0 >= (uint32_t)WAVES;
+  auto one_band_sum = [&](uint32_t band) {
     if (tc == t1) FLS_STAMP(p.out.flags, 256 + blockIdx.x, wave);
 #pragma unroll
     for (int rb = 0; rb < kRowBlocks; ++rb) *(float4v*)(tile + rb * 1024 + lane * 16) = acc[rb][0];
@@ -278,14 +280,22 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     if (lane == 0) arrived = __hip_atomic_fetch_add(&red->cnt[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     if (__builtin_amdgcn_readfirstlane(arrived) != (uint32_t)WAVES - 1) return;
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-    float4v sum[kRowBlocks][NB];
 #pragma unroll
-    for (int rb = 0; rb < kRowBlocks; ++rb) sum[rb][0] = float4v{0.f, 0.f, 0.f, 0.f};
+    for (int rb = 0; rb < kRowBlocks; ++rb) acc[rb][0] = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int w = 0; w < WAVES; ++w)
 #pragma unroll
-      for (int rb = 0; rb < kRowBlocks; ++rb) sum[rb][0] += *(const float4v*)(lds + w * kWaveLds + rb * 1024 + lane * 16);
-    store_band<NB>(p.out, sum, band, lane);
+      for (int rb = 0; rb < kRowBlocks; ++rb) acc[rb][0] += *(const float4v*)(lds + w * kWaveLds + rb * 1024 + lane * 16);
+    const bool from_start = share0 % KT == 0, to_end = share1 % KT == 0;
+    if ((from_start && to_end) || (FLS_ABLATE & 64)) {
+      store_band<NB>(p.out, acc, band, lane);
+    } else if (from_start) {
+      hs.own = true;  // finished after the loop, once the other workgroups' sums are there
+      hs.own_band = band;
+    } else {
+      store_partial<NB>(p.out, acc, blockIdx.x, lane);
+      hs.publish = true;
+    }
   };
 
   if (WAVES > 4 && wave >= WAVES / 2) __builtin_amdgcn_s_setprio(1);
@@ -303,7 +313,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 #pragma unroll
     for (int i = 0; i < NS - 1; ++i)
       if (tc < pend) step(s[i], x[i], sb[i], se[i]);
-    if (band_aligned) whole_band_sum(bandc);
+    if (one_band) one_band_sum(bandc);
     else hand_over(bandc, pend - piece0);
     ktc += pend - piece0;
     if (ktc == KT) {
