@@ -270,6 +270,22 @@ def test_full_size_c2_sampled_rows_and_blob(fls, oracle_mod):
         assert _rel_err(C[:, m0:m1], ref) <= TOL
 
 
+@pytest.mark.parametrize("name", ["C3", "C4"])
+def test_full_size_other_configs_sampled_rows(fls, oracle_mod, name):
+    """C3 (N = 32, two column blocks per wave) and C4 (N = 64: the 64-column pass with K slices and the second,
+    adding kernel) at their full sizes: the blob's size and header against the oracle's count, C on sampled row
+    bands (first, inner, last) that the oracle computes row by row."""
+    cfg = wl.CONFIGS[name]
+    W, X = wl.make_inputs(cfg)
+    blob, st, C = _run_spmm(fls, W, X, cfg.N)
+    assert st["nnz"] == int(np.count_nonzero(W))
+    bands = cfg.M // 128
+    for band in (0, bands // 3, bands - 1):
+        m0, m1 = band * 128, band * 128 + 128
+        ref = oracle_mod.ref_spmm_f64(W, X, rows=(m0, m1))[:, m0:m1]
+        assert _rel_err(C[:, m0:m1], ref) <= TOL
+
+
 def test_back_to_back_shapes_share_one_workspace(fls, oracle_mod):
     """Calls of different shapes and widths, alternating, on one registered workspace: epochs advance per launch,
     nothing is cleared in between, and the kernels' error word (a hand-over wait that gave up) stays 0."""
