@@ -385,7 +385,10 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
   if (a.max_tile_words <= 2 * 256) R = 2;
   else if (a.max_tile_words <= 4 * 256) R = 4;
   else if (a.max_tile_words <= 6 * 256) R = 6;
-  if (a.N > kGroupCols) {
+  // The 64-column pass stages at most 2048 words of a tile (it has no slow path for more): a
+  // matrix with denser tiles - less than half sparse somewhere - takes 32-column passes throughout.
+  const bool wide_ok = a.max_tile_words <= 8 * 256;
+  if (a.N > kGroupCols && wide_ok) {
     hipError_t e = launch_xpack(a, stream);  // the 64-column passes read X from a copy in fragment order
     if (e != hipSuccess) return e;
   }
@@ -399,7 +402,7 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
       p.X = a.X;
       e = launch_r<1, 8>(R, p, grid, stream);
       n0 += 16;
-    } else if (left <= 32) {
+    } else if (left <= 32 || !wide_ok) {
       p.X = a.X;
       e = launch_r<2, 8>(R, p, grid, stream);
       n0 += 32;

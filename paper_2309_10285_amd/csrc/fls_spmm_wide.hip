@@ -21,7 +21,6 @@
 // behind those reads, and runs its MFMAs spread between the extraction's instructions.
 #include "fls_device.h"
 #include "fls_launch.h"
-#include "fls_tile.h"
 
 namespace fls {
 
@@ -138,8 +137,12 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   };
 
   // extract (Alg. 2), branch-free so that a step is one basic block: lanes past the end of the
-  // run (their loads returned 0) are pointed at the slot that padding words go to
-  auto extract = [&](const u32x4(&s)[R], uint32_t begin, uint32_t end) {
+  // run (their loads returned 0) are pointed at the slot that padding words go to.  The words are
+  // then replaced by the LDS addresses they went to, which is all the later re-zeroing needs.
+  // (No tile has more than R * 256 words: the launcher sends denser matrices to the narrow kernel.)
+  typedef __attribute__((address_space(3))) uint16_t* lds_u16_ptr;
+  const uint32_t tile_addr = (uint32_t)(uintptr_t)tile;  // LDS addresses are the low 32 bits
+  auto extract = [&](u32x4(&s)[R], uint32_t begin, uint32_t end) {
     const uint32_t n = end - begin;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -147,10 +150,11 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const uint32_t w = valid ? s[r][j] : (uint32_t)kTileElems;
-        *(uint16_t*)(tile + ((w & 0xffffu) << 1)) = (uint16_t)(w >> 16);
+        const uint32_t addr = tile_addr + ((w & 0xffffu) << 1);
+        *(lds_u16_ptr)(uintptr_t)addr = (uint16_t)(w >> 16);
+        s[r][j] = addr;
       }
     }
-    if (n > R * 256u) extract_overflow(p.words, begin + R * 256u, end, tile);
   };
 
   const unsigned char* frag = tile + ((lane >> 4) * kTileM + (lane & 15)) * 16;
@@ -161,28 +165,18 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   // rst_smem.  Sparse tiles (R <= 4: at most 1024 words) are re-zeroed by storing zeros where
   // their words went - as many 2 B stores as the extraction - instead of clearing all 8 KB.
   constexpr bool kUnscatter = R <= 4;
-  auto unscatter = [&](const u32x4(&s)[R], uint32_t begin, uint32_t end) {
-    const uint32_t n = end - begin;
-    if (n > R * 256u) {  // the overflow path wrote words this wave no longer holds (never, if the header is honest)
+  auto unscatter = [&](const u32x4(&s)[R]) {
 #pragma unroll
-      for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
-    }
+    for (int r = 0; r < R; ++r)
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const bool valid = (r * 64 + lane) * 4u < n;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint32_t w = valid ? s[r][j] : (uint32_t)kTileElems;
-        *(uint16_t*)(tile + ((w & 0xffffu) << 1)) = (uint16_t)0;
-      }
-    }
+      for (int j = 0; j < 4; ++j) *(lds_u16_ptr)(uintptr_t)s[r][j] = (uint16_t)0;
   };
 
   // One tile, whose words stage `cur` still holds and which the step before extracted into LDS:
   // its fragments are read (A from the wave's tile, B from the X chunk), the tile is re-zeroed
   // behind the reads, stage `cur` is refilled, the next tile (stage `nxt`) is extracted, and the
   // MFMAs run spread between those instructions.
-  auto step = [&](u32x4(&cur)[R], uint32_t& cb, uint32_t& ce, const u32x4(&nxt)[R], uint32_t nb_, uint32_t ne_,
+  auto step = [&](u32x4(&cur)[R], uint32_t& cb, uint32_t& ce, u32x4(&nxt)[R], uint32_t nb_, uint32_t ne_,
                   const unsigned char* xt) {
     half8 fa[kRowBlocks], fb[NB];
 #pragma unroll
@@ -190,7 +184,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
 #pragma unroll
     for (int j = 0; j < kRowBlocks; ++j) fa[j] = *(const half8*)(frag + j * 256);
     if constexpr (kUnscatter) {
-      unscatter(cur, cb, ce);
+      unscatter(cur);
     } else {
 #pragma unroll
       for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
