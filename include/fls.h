@@ -127,7 +127,10 @@ int fls_set_workspace(void* ws_dev, size_t bytes, fls_stream_t stream);
  *   X_dev  in : fp16 column-major K x N;  C_dev out: fp16 column-major M x N (fully overwritten)
  * The first call on a given blob address reads its 64-byte header back (a blocking copy) to
  * validate it and to pick the kernel variant; later calls on that address do not.  Call
- * fls_forget after overwriting a blob in place with a different one.
+ * fls_forget when the memory at that address comes to hold a different blob by other means than
+ * fls_compress (a copy, a freed buffer handed out again).  A remembered header that is out of date
+ * but of the same M, K costs speed only (a variant sized for other tile lengths, down to a plain
+ * slow path); the kernels take every tile's length from the blob itself.
  * Errors: FLS_EINVAL, FLS_EALIGN, FLS_EFORMAT, FLS_EWORKSPACE, FLS_EHIP.
  */
 int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int64_t K, int64_t N,

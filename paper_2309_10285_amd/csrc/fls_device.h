@@ -30,6 +30,9 @@ constexpr int kTileElems = kTileM * kTileK;
 constexpr int kTileBytes = kTileElems * 2;  // dense fp16 tile in LDS
 constexpr int kRowBlocks = kTileM / 16;     // 16-row MFMA blocks per tile
 
+constexpr int kHeaderWords = 16;            // the blob's 64-byte header, in 32-bit words; TileOffsets follow it
+constexpr int kHeaderMaxTileWords = 6;      // header word that holds the length of the longest tile
+
 constexpr int kAccPerBlock = kTileM * 16;   // fp32 values of one 128 x 16 column block
 constexpr int kMaxGrid = 512;               // workgroups a launch may use (sizes the workspace)
 constexpr int kBufferFlags = 0x00020000;    // raw buffer, 32-bit data format (gfx9 descriptor word 3)

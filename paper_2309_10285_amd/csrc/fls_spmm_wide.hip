@@ -139,7 +139,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   // extract (Alg. 2), branch-free so that a step is one basic block: lanes past the end of the
   // run (their loads returned 0) are pointed at the slot that padding words go to.  The words are
   // then replaced by the LDS addresses they went to, which is all the later re-zeroing needs.
-  // (No tile has more than R * 256 words: the launcher sends denser matrices to the narrow kernel.)
+  // (No tile has more than R * 256 words here: see `densest` below.)
   typedef __attribute__((address_space(3))) uint16_t* lds_u16_ptr;
   const uint32_t tile_addr = (uint32_t)(uintptr_t)tile;  // LDS addresses are the low 32 bits
   auto extract = [&](u32x4(&s)[R], uint32_t begin, uint32_t end) {
@@ -204,38 +204,72 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
     }
   };
 
-  // prologue: ring filled, first tile in LDS, first X chunk in LDS
-  xload(xr, 0);
+  // The launcher picks R from the header the host remembers for this blob address.  If the memory
+  // holds a denser blob by now (one written there without the library's knowing), the ring cannot
+  // stage its tiles: the whole grid then takes a plain path - tile by tile, words straight from
+  // memory into LDS, X fragments from the packed copy - which is slow and right.
+  const uint32_t densest = offs[kHeaderMaxTileWords - kHeaderWords];
+  if (densest > R * 256u) {
+    for (uint32_t t = t0; t < t1; ++t) {
+      const uint32_t begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)offs[t]);
+      const uint32_t end = (uint32_t)__builtin_amdgcn_readfirstlane((int)offs[t + 1]);
+      for (uint32_t i = begin + (uint32_t)lane * 4u; i < end; i += 256u) {
+        const u32x4 w = *(const u32x4*)(p.words + i);
 #pragma unroll
-  for (int i = 0; i < NS; ++i) issue(s[i], sb[i], se[i]);
-  uint32_t next_window = window_at(t0 + NS);
-  extract(s[0], sb[0], se[0]);
-  xstore(xr, 0);
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-  __builtin_amdgcn_s_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-
-  constexpr int kChunksPerBody = NS / kWideWaves;
-  for (uint32_t body = 0; body < bodies; ++body) {
-    // refills of this body ask for tiles t0 + NS * body + NS ... + 2 NS - 1: inside the window
-    // that starts at t0 + NS * (body + 1)
-    window = next_window;
-    wbase = t0 + NS * (body + 1);
-    next_window = window_at(t0 + NS * (body + 2));
-#pragma unroll
-    for (int c = 0; c < kChunksPerBody; ++c) {
-      const uint32_t chunk = body * kChunksPerBody + c;
-      xload(xr, chunk + 1);
-#pragma unroll
-      for (int j = 0; j < kWideWaves; ++j) {
-        const int i = c * kWideWaves + j, i1 = (i + 1) % NS;  // stages of this tile and of the next
-        step(s[i], sb[i], se[i], s[i1], sb[i1], se[i1], xbuf + (chunk & 1u) * kXChunkBytes + j * kXTileBytes);
+        for (int j = 0; j < 4; ++j) *(uint16_t*)(tile + ((w[j] & 0xffffu) << 1)) = (uint16_t)(w[j] >> 16);
       }
-      xstore(xr, (chunk + 1) & 1u);
-      // the chunk just written is complete, and nobody still reads the one written next
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-      __builtin_amdgcn_s_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+      const uint32_t kt = k0 + (t - t0);
+      half8 fa[kRowBlocks], fb[NB];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(
+            xrsrc, (uint32_t)nb < xvalid ? kt * xblocks * 1024u + xlane + nb * 1024u : 0xffffff00u, 0, 0);
+        fb[nb] = __builtin_bit_cast(half8, v);
+      }
+#pragma unroll
+      for (int j = 0; j < kRowBlocks; ++j) fa[j] = *(const half8*)(frag + j * 256);
+#pragma unroll
+      for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
+#pragma unroll
+      for (int j = 0; j < kRowBlocks; ++j)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+          acc[j][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[j], fb[nb], acc[j][nb], 0, 0, 0);
+    }
+  } else {
+    // prologue: ring filled, first tile in LDS, first X chunk in LDS
+    xload(xr, 0);
+#pragma unroll
+    for (int i = 0; i < NS; ++i) issue(s[i], sb[i], se[i]);
+    uint32_t next_window = window_at(t0 + NS);
+    extract(s[0], sb[0], se[0]);
+    xstore(xr, 0);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+
+    constexpr int kChunksPerBody = NS / kWideWaves;
+    for (uint32_t body = 0; body < bodies; ++body) {
+      // refills of this body ask for tiles t0 + NS * body + NS ... + 2 NS - 1: inside the window
+      // that starts at t0 + NS * (body + 1)
+      window = next_window;
+      wbase = t0 + NS * (body + 1);
+      next_window = window_at(t0 + NS * (body + 2));
+#pragma unroll
+      for (int c = 0; c < kChunksPerBody; ++c) {
+        const uint32_t chunk = body * kChunksPerBody + c;
+        xload(xr, chunk + 1);
+#pragma unroll
+        for (int j = 0; j < kWideWaves; ++j) {
+          const int i = c * kWideWaves + j, i1 = (i + 1) % NS;  // stages of this tile and of the next
+          step(s[i], sb[i], se[i], s[i1], sb[i1], se[i1], xbuf + (chunk & 1u) * kXChunkBytes + j * kXTileBytes);
+        }
+        xstore(xr, (chunk + 1) & 1u);
+        // the chunk just written is complete, and nobody still reads the one written next
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+      }
     }
   }
 

@@ -327,3 +327,34 @@ def test_very_long_k(fls, oracle_mod):
             assert np.array_equal(blob.cpu().numpy(), ref_blob)
         assert _rel_err(C, oracle_mod.ref_spmm_f64(W, X)) <= TOL
     assert _rel_err(_run_dense(fls, W, X[:16], 16), oracle_mod.ref_spmm_f64(W, X[:16])) <= TOL
+
+
+@pytest.mark.parametrize("N", [16, 64, 100])
+def test_blob_replaced_in_place_behind_the_librarys_back(fls, oracle_mod, N):
+    """A sparse blob is used at an address, then the bytes of a denser blob of the same shape are copied over it
+    without fls_forget: the kernel variant is still picked for the sparse one (a ring too short for the new tiles),
+    and the results must be right all the same, in the 32-column passes and in the 64-column pass.  Then the other
+    way round (a ring longer than needed)."""
+    import torch
+
+    M, K = 1024, 2048
+    W32 = wl.gen_weights_f32(M, K, 41)
+    sparse, dense = wl.prune_uniform(W32, 0.9, 42), wl.prune_uniform(W32, 0.45, 43)
+    X = wl.gen_x(N, K, 44)
+    Xd = torch.from_numpy(X.view(np.float16)).cuda()
+    blob_s, st_s = fls.fls_compress(_dev_w(sparse))
+    blob_d, st_d = fls.fls_compress(_dev_w(dense))
+    assert st_s["max_tile_words"] <= 1024 and st_d["max_tile_words"] > 2048
+    blob_s, blob_d = blob_s.clone(), blob_d.clone()
+    place = torch.zeros(max(blob_s.numel(), blob_d.numel()), dtype=torch.uint8, device="cuda")
+    fls.ensure_workspace(M, K, N)
+    for first, second, W_second in ((blob_s, blob_d, dense), (blob_d, blob_s, sparse)):
+        fls.fls_forget(place)
+        place[:first.numel()].copy_(first)
+        C = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+        fls.fls_spmm(place, Xd, C, M, K, N)  # the header of `first` is remembered for this address from here on
+        place[:second.numel()].copy_(second)
+        fls.fls_spmm(place, Xd, C, M, K, N)
+        torch.cuda.synchronize()
+        assert _rel_err(C.cpu().numpy(), oracle_mod.ref_spmm_f64(W_second, X)) <= TOL
+    fls.fls_forget(place)
