@@ -122,6 +122,84 @@ def run_sweep(args):
         raise SystemExit(f"sweep: a point is off the oracle by {worst:.3g} (tolerance 2e-3)")
 
 
+def _run_layer_on_stream(args, torch, wl, fls, side):
+    N, beta = args.layer_n, 0.8
+    mats = wl.decoder_layer(7168, 28672, N, beta)
+    fls.ensure_workspace(max(c.M for c in mats), max(c.K for c in mats), N)
+    copies = 3
+    sparse, dense, recs = [], [], []
+    for cfg in mats:
+        W32 = wl.make_w32(cfg)
+        Wb, Xb = wl.make_inputs(cfg, W32)
+        X = torch.from_numpy(Xb.view(np.float16)).cuda()
+        blob0, st = fls.fls_compress(torch.from_numpy(Wb.view(np.float16)).cuda())
+        blobs = [blob0.clone() for _ in range(copies)]
+        del blob0
+        Wd = torch.from_numpy(wl.dense_bits(W32).view(np.float16)).cuda()
+        Wds = [Wd] + [Wd.clone() for _ in range(copies - 1)]
+        C = torch.empty((N, cfg.M), dtype=torch.float16, device="cuda")
+        D = torch.empty((N, cfg.M), dtype=torch.float16, device="cuda")
+        sparse.append([fls.prepare_spmm(b, X, C, cfg.M, cfg.K, N) for b in blobs])
+        dense.append([fls.prepare_dense_gemm(w, X, D, cfg.M, cfg.K, N) for w in Wds])
+        ms, _ = _time_loop(sparse[-1], args.steps, args.warmup)
+        dms, _ = _time_loop(dense[-1], args.steps, args.warmup)
+        err = None
+        if not args.no_cpu_baseline:
+            import oracle
+
+            ref = oracle.ref_spmm_f64(Wb, Xb, rows=(0, 256))[:, :256]
+            err = float(np.abs(C.cpu().numpy()[:, :256].astype(np.float64) - ref).max() / np.abs(ref).max())
+        alg = st["bytes_total"] + 2 * cfg.K * N + 2 * cfg.M * N
+        recs.append({"matmul": cfg.what, "M": cfg.M, "K": cfg.K, "nnz": st["nnz"], "alone_us": round(ms * 1e3, 2),
+                     "alone_GBps": round(alg / ms / 1e6, 1), "dense_alone_us": round(dms * 1e3, 2),
+                     "algorithmic_bytes": alg, "max_rel_err_first_256_rows": err})
+
+    def layer_calls(table):
+        return [lambda c=c, table=table: [calls[c]() for calls in table] for c in range(copies)]
+
+    def graph_of(table):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for c in range(copies):
+                for calls in table:
+                    calls[c]()
+        return g
+
+    layer_steps = max(50, args.steps // 4)
+    out = {"mode": "decoder layer", "model": "OPT-30B-shaped (hidden 7168, FFN 28672)", "N": N, "sparsity": beta,
+           "weight_copies_rotated": copies, "layers_timed": layer_steps, "matmuls": recs}
+    for name, table in (("spmm", sparse), ("dense", dense)):
+        ms, _ = _time_loop(layer_calls(table), layer_steps, max(10, args.warmup // 4))
+        out[f"{name}_layer_us_eager"] = round(ms * 1e3, 2)
+        g = graph_of(table)
+        gms, _ = _time_loop([g.replay], max(20, layer_steps // copies), 5)
+        out[f"{name}_layer_us_graph"] = round(gms * 1e3 / copies, 2)
+    alg = sum(r["algorithmic_bytes"] for r in recs)
+    out["spmm_layer_GBps_graph"] = round(alg / out["spmm_layer_us_graph"] / 1e3, 1)
+    out["spmm_layer_hbm_frac_graph"] = round(alg / out["spmm_layer_us_graph"] / 1e3 / HBM_PEAK_GBS, 4)
+    out["sum_of_alone_us"] = round(sum(r["alone_us"] for r in recs), 2)
+    out["layer_speedup_vs_dense_graph"] = round(out["dense_layer_us_graph"] / out["spmm_layer_us_graph"], 3)
+    return out
+
+
+def run_layer(args):
+    """The four weight MatMuls of one OPT-30B-shaped decoder layer (hidden 7168, FFN 28672) back to back on one
+    stream, as eager calls and as one HIP graph, against the same four dense GEMMs.  One JSON line (not the bench
+    line).  The layers in a timed sequence rotate over copies of the weights (more than 1 GB in total)."""
+    import torch
+
+    import fls_workloads as wl
+    import paper_2309_10285_amd as fls
+
+    fls.lib()
+    # a stream of its own: the null stream cannot be captured into a graph, and prepared calls stay bound to the
+    # stream that was current when they were prepared
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        out = _run_layer_on_stream(args, torch, wl, fls, side)
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -134,6 +212,10 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the bench line: the 12288 x 12288 sweep (sparsity x mask x N, each with its dense pair)")
     ap.add_argument("--out", default="", help="with --sweep: also write the lines to this file")
+    ap.add_argument("--layer", action="store_true",
+                    help="instead of the bench line: the four MatMuls of one OPT-30B-shaped decoder layer back to back, "
+                         "eager and as a HIP graph")
+    ap.add_argument("--layer-n", type=int, default=16, help="with --layer: the batch size N")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (the known-size kernel the HBM counters "
                          "of a rocprofv3 --pmc run are scaled by)")
@@ -143,6 +225,9 @@ def main():
 
     if args.sweep:
         run_sweep(args)
+        return
+    if args.layer:
+        run_layer(args)
         return
 
     import torch

@@ -102,6 +102,15 @@ CONFIGS = {
     "L2": Config("L2", 49152, 12288, 8, 0.70, "magnitude", 0x5EED0007, "OPT-175B-shaped FFN up-projection"),
 }
 
+
+def decoder_layer(hidden, ffn, N, beta, seed=0x5EED0010):
+    """The four weight MatMuls of one OPT decoder layer (Sec. 2.1 / Fig. 2 of the paper): fused QKV projection,
+    attention output projection, the two feed-forward layers.  Each has its own seeded weights and activations."""
+    shapes = [("QKV projection", 3 * hidden, hidden), ("attention output projection", hidden, hidden),
+              ("FFN up-projection", ffn, hidden), ("FFN down-projection", hidden, ffn)]
+    return [Config(f"layer-{i}", M, K, N, beta, "magnitude", seed + 16 * i, what) for i, (what, M, K) in enumerate(shapes)]
+
+
 SWEEP_M = 12288
 SWEEP_K = 12288
 SWEEP_BETAS = (0.5, 0.6, 0.7, 0.8, 0.9)

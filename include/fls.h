@@ -112,9 +112,9 @@ size_t fls_workspace_bytes(int64_t M, int64_t K, int64_t N);
 /*
  * Registers a caller-owned workspace (16-byte aligned) and clears it on `stream`.  The
  * workspace must stay valid, and untouched by the caller, until replaced.  Nothing has to be
- * cleared between calls (flags carry a per-launch number), so one registration serves any
- * number of calls of any shape it is large enough for; calls that share it must not overlap
- * in time.  Errors: FLS_EINVAL, FLS_EALIGN, FLS_EHIP.
+ * cleared between calls (every launch leaves the flags it raised lowered again), so one
+ * registration serves any number of calls of any shape it is large enough for; calls that share
+ * it must not overlap in time.  Errors: FLS_EINVAL, FLS_EALIGN, FLS_EHIP.
  */
 int fls_set_workspace(void* ws_dev, size_t bytes, fls_stream_t stream);
 
@@ -131,6 +131,9 @@ int fls_set_workspace(void* ws_dev, size_t bytes, fls_stream_t stream);
  * fls_compress (a copy, a freed buffer handed out again).  A remembered header that is out of date
  * but of the same M, K costs speed only (a variant sized for other tile lengths, down to a plain
  * slow path); the kernels take every tile's length from the blob itself.
+ * Stream capture: a call on a blob address the library already knows enqueues kernels only (no
+ * copies, no memsets, no host-side per-launch state in their arguments), so it may be recorded
+ * into a HIP graph and replayed; make one ordinary call on that address and shape first.
  * Errors: FLS_EINVAL, FLS_EALIGN, FLS_EFORMAT, FLS_EWORKSPACE, FLS_EHIP.
  */
 int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int64_t K, int64_t N,

@@ -98,24 +98,12 @@ int check_mm_args(const void* W, const void* X, void* C, int64_t M, int64_t K, i
 }
 
 // Workspace: a fixed 4 MiB control area (one u32 flag per workgroup and an error word; the rest
-// is spare), then the split-K partial slots (fp32).  The control area has the same place for
-// every shape, so partial sums of one call can never be read as flags by the next.
+// is spare; cleared when the workspace is registered, and every launch leaves its flags cleared),
+// then the split-K partial slots (fp32), then, for N > 32, X repacked into MFMA fragment order
+// (K x N rounded up to 16 columns, fp16).  The control area has the same place for every shape, so
+// partial sums of one call can never be read as flags by the next.
 constexpr size_t kCounterAreaBytes = (size_t)4 << 20;
-uint32_t g_epoch = 0;  // launches since the workspace was registered; a flag equal to it is current
 
-// Reserves `count` launch numbers (call with g_mu held).  Before the 32-bit counter could wrap,
-// the control area is cleared again on the call's stream and the count restarts, so that a launch
-// number is never 0 and never meets a flag left by the launch 2^32 numbers earlier.
-int reserve_epochs(uint32_t count, hipStream_t stream, uint32_t* first) {
-  if (g_epoch > 0xffff0000u) {
-    if (fls::launch_fill_zero(g_ws, kCounterAreaBytes, stream) != hipSuccess) return FLS_EHIP;
-    g_epoch = 0;
-  }
-  *first = g_epoch + 1;
-  g_epoch += count;
-  return FLS_OK;
-}
-// then, for N > 32, X repacked into MFMA fragment order (K x N rounded up to 16 columns, fp16).
 void workspace_layout(int64_t K, int64_t N, size_t* total, size_t* xpack_offset) {
   const size_t parts = fls::parts_floats((uint32_t)N) * sizeof(float);
   if (xpack_offset) *xpack_offset = kCounterAreaBytes + parts;
@@ -198,7 +186,6 @@ int fls_set_workspace(void* ws_dev, size_t bytes, fls_stream_t stream) {
   std::lock_guard<std::mutex> lk(g_mu);
   g_ws = ws_dev;
   g_ws_bytes = bytes;
-  g_epoch = 0;
   return FLS_OK;
 }
 
@@ -215,15 +202,12 @@ int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int6
   size_t need, xpack_offset;
   workspace_layout(K, N, &need, &xpack_offset);
   void* ws;
-  uint32_t epoch0;
   BlobInfo info;
   bool known;
   {
     std::lock_guard<std::mutex> lk(g_mu);
     if (!g_ws || g_ws_bytes < need) return FLS_EWORKSPACE;
     ws = g_ws;
-    rc = reserve_epochs(fls::column_groups((uint32_t)N), (hipStream_t)stream, &epoch0);  // one launch per column group at most
-    if (rc != FLS_OK) return rc;
     auto it = g_blobs.find(Wc_dev);
     known = it != g_blobs.end();
     if (known) info = it->second;
@@ -249,7 +233,6 @@ int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int6
   a.X = (const _Float16*)X_dev;
   a.C = (_Float16*)C_dev;
   a.flags = (uint32_t*)ws;
-  a.epoch0 = epoch0;
   a.parts = (float*)((unsigned char*)ws + kCounterAreaBytes);
   a.xpack = (_Float16*)((unsigned char*)ws + xpack_offset);
   a.M = (uint32_t)M;
@@ -267,13 +250,10 @@ int fls_dense_gemm(const void* W_dev, const void* X_dev, void* C_dev, int64_t M,
   size_t need;
   workspace_layout(K, N, &need, nullptr);
   void* ws;
-  uint32_t epoch0;
   {
     std::lock_guard<std::mutex> lk(g_mu);
     if (!g_ws || g_ws_bytes < need) return FLS_EWORKSPACE;
     ws = g_ws;
-    rc = reserve_epochs(fls::column_groups((uint32_t)N), (hipStream_t)stream, &epoch0);
-    if (rc != FLS_OK) return rc;
   }
   const int cus = num_cus();
   if (cus <= 0) return FLS_EHIP;
@@ -282,7 +262,6 @@ int fls_dense_gemm(const void* W_dev, const void* X_dev, void* C_dev, int64_t M,
   a.X = (const _Float16*)X_dev;
   a.C = (_Float16*)C_dev;
   a.flags = (uint32_t*)ws;
-  a.epoch0 = epoch0;
   a.parts = (float*)((unsigned char*)ws + kCounterAreaBytes);
   a.M = (uint32_t)M;
   a.K = (uint32_t)K;

@@ -163,7 +163,6 @@ hipError_t launch_dense(const DenseLaunch& a, hipStream_t stream) {
   const int grid = pick_grid(a.M / kTileM, a.K / kTileK, a.num_cus);
   for (uint32_t n0 = 0; n0 < a.N; n0 += kGroupCols) {
     p.out.n0 = n0;
-    p.out.epoch = a.epoch0 + n0 / kGroupCols;
     const uint32_t ncols = a.N - n0 < kGroupCols ? a.N - n0 : kGroupCols;
     hipError_t e;
     const uint32_t h = ncols <= 16 ? 2 : 1;

@@ -52,12 +52,11 @@ constexpr int kAuxCoherent = 16;            // sc1: device scope - through to me
 struct OutParams {
   _Float16* C;      // column-major M x N
   float* parts;     // [workgroup][NB * 2048] fp32 partial sums in accumulator order
-  uint32_t* flags;  // [workgroup] epoch of the last published partial sum; [kMaxGrid] error word
+  uint32_t* flags;  // [workgroup] 1 while a published partial sum waits for its band's owner; [kMaxGrid] error word
   uint32_t M, N;    // N = columns of the whole problem
   uint32_t n0;      // first column of this launch's column group
   uint32_t KT;      // K tiles per band
   uint32_t T;       // tiles in total
-  uint32_t epoch;   // this launch's number (never 0)
 };
 
 // First tile of workgroup q's share when T tiles are cut over P workgroups.
@@ -180,14 +179,16 @@ __device__ __forceinline__ void wg_reduce_skip(WgReduceLds<NB>* red, uint32_t se
 // the band's first tile.  The owner's piece of the band is the last thing in its share, so its
 // sum is still in registers when its run ends.  Every other workgroup that holds tiles of the
 // band stores its sum to its slot when its piece ends (plain write-through stores, nothing waits
-// for them) and publishes the slot when its own run ends, by writing the call's epoch number to
-// its flag after the stores were acknowledged.  The owner then polls those flags, adds the slots
-// in workgroup order (so the result does not depend on timing) and writes fp16 C.
+// for them) and publishes the slot when its own run ends, by raising its flag after the stores
+// were acknowledged.  The owner then polls those flags, adds the slots in workgroup order (so the
+// result does not depend on timing) and writes fp16 C.
 //
 // Partial sums cross between the L2 caches of different XCDs: they are written through to memory
 // and read past the caches access by access (sc1 on the instruction), so no cache-wide write-back
-// or invalidate - what a device-scope fence costs - is needed.  Flags compare against an epoch
-// that the host advances with every launch, so nothing has to be cleared between calls.
+// or invalidate - what a device-scope fence costs - is needed.  A workgroup publishes at most one
+// partial sum per launch (only the first band of a share can begin outside it) and exactly one
+// owner waits for it; the owner lowers the flag it has seen, so all flags are down again when the
+// launch ends: nothing is cleared between calls, and a launch recorded in a graph can be replayed.
 //
 // A workgroup publishes before it polls, and only polls workgroups of higher index, so the wait
 // ends as soon as those workgroups have run; the spin is bounded all the same.
@@ -209,7 +210,7 @@ __device__ __forceinline__ void store_partial(const OutParams& o, const float4v 
 // By the wave that called store_partial, once its run is over.
 __device__ __forceinline__ void publish_partial(const OutParams& o, uint32_t wg, int lane) {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // s_waitcnt vmcnt(0): the stores are acknowledged
-  if (lane == 0) __hip_atomic_store(o.flags + wg, o.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (lane == 0) __hip_atomic_store(o.flags + wg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // acc holds the owner's own sum for `band`; adds the other workgroups' and writes C.
@@ -220,13 +221,17 @@ __device__ __forceinline__ void owner_finish(const OutParams& o, float4v (&acc)[
   for (uint32_t q = wg + 1; q < P && share_begin(q, o.T, P) < band_hi; ++q) {
     if (share_begin(q + 1, o.T, P) == share_begin(q, o.T, P)) continue;  // empty share: no contribution
     uint32_t spins = 0;
-    while (__hip_atomic_load(o.flags + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != o.epoch) {
+    bool seen = true;
+    while (__hip_atomic_load(o.flags + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
       __builtin_amdgcn_s_sleep(8);
       if (++spins == kSpinLimit) {  // never seen; gives up rather than hang, and says so
         if (lane == 0) __hip_atomic_store(o.flags + kMaxGrid, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        seen = false;
         break;
       }
     }
+    // workgroup q raises its flag once per launch and nobody else looks at it: down again for the next launch
+    if (seen && lane == 0) __hip_atomic_store(o.flags + q, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   FLS_STAMP(o.flags, wg, 6);
   // As many loads as the registers allow are issued before the first is used: each is a trip

@@ -13,7 +13,6 @@ struct SpmmLaunch {
   float* parts;
   uint32_t* flags;
   _Float16* xpack;  // workspace area of xpack_bytes(K, N) for X in MFMA fragment order (used when N > 32)
-  uint32_t epoch0;  // launch number of the first column group (the next groups count on)
   uint32_t M, K, N;
   uint32_t max_tile_words;
   int num_cus;
@@ -25,7 +24,6 @@ struct DenseLaunch {
   _Float16* C;
   float* parts;
   uint32_t* flags;
-  uint32_t epoch0;  // launch number of the first column group (the next groups count on)
   uint32_t M, K, N;
   int num_cus;
 };
@@ -43,7 +41,6 @@ struct CompressLaunch {
 // per workgroup with the whole register file each).
 constexpr uint32_t kGroupCols = 32;
 constexpr uint32_t kSpmmGroupCols = 64;
-inline uint32_t column_groups(uint32_t N) { return (N + kGroupCols - 1) / kGroupCols; }  // upper bound on launches per call
 inline uint32_t group_blocks(uint32_t ncols) { return ncols <= 16 ? 1u : (ncols <= 32 ? 2u : 4u); }
 constexpr uint32_t kMaxWorkgroups = 512;    // must equal fls::kMaxGrid of the device code
 // The 64-column pass of the sparse kernel cuts its work as (group of 4 bands) x (K slice) and

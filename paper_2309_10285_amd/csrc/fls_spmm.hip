@@ -392,10 +392,8 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
     hipError_t e = launch_xpack(a, stream);  // the 64-column passes read X from a copy in fragment order
     if (e != hipSuccess) return e;
   }
-  uint32_t launches = 0;
   for (uint32_t n0 = 0; n0 < a.N;) {
     p.out.n0 = n0;
-    p.out.epoch = a.epoch0 + launches++;
     const uint32_t left = a.N - n0;
     hipError_t e;
     if (left <= 16) {

@@ -287,7 +287,7 @@ def test_full_size_other_configs_sampled_rows(fls, oracle_mod, name):
 
 
 def test_back_to_back_shapes_share_one_workspace(fls, oracle_mod):
-    """Calls of different shapes and widths, alternating, on one registered workspace: epochs advance per launch,
+    """Calls of different shapes and widths, alternating, on one registered workspace: flags raised by a launch are lowered by it,
     nothing is cleared in between, and the kernels' error word (a hand-over wait that gave up) stays 0."""
     import torch
 
@@ -358,3 +358,48 @@ def test_blob_replaced_in_place_behind_the_librarys_back(fls, oracle_mod, N):
         torch.cuda.synchronize()
         assert _rel_err(C.cpu().numpy(), oracle_mod.ref_spmm_f64(W_second, X)) <= TOL
     fls.fls_forget(place)
+
+
+def test_calls_recorded_in_a_graph_replay_right(fls, oracle_mod):
+    """fls_spmm (32-column pass with bands cut between workgroups, 64-column pass) and fls_dense_gemm recorded
+    into one HIP graph: every replay, with new contents in X and eager calls in between, must match the oracle -
+    nothing in a launch's arguments may go stale (the hand-over flags are lowered by the launch that raised them)."""
+    import torch
+
+    M, K = 384, 8192  # 3 bands over all CUs: every band's sum crosses workgroups
+    W = wl.prune_uniform(wl.gen_weights_f32(M, K, 51), 0.85, 52)
+    blob, _ = fls.fls_compress(_dev_w(W))
+    Wd = _dev_w(W)
+    fls.ensure_workspace(M, K, 80)
+    Xs = {N: wl.gen_x(N, K, 53 + N) for N in (16, 80)}
+    Xd = {N: torch.from_numpy(Xs[N].view(np.float16)).cuda() for N in Xs}
+    Cs = {N: torch.zeros((N, M), dtype=torch.float16, device="cuda") for N in Xs}
+    D = torch.zeros((16, M), dtype=torch.float16, device="cuda")
+    for N in Xs:  # ordinary calls first: headers read, kernel attributes set
+        fls.fls_spmm(blob, Xd[N], Cs[N], M, K, N)
+    fls.fls_dense_gemm(Wd, Xd[16], D, M, K, 16)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for N in Xs:
+            fls.fls_spmm(blob, Xd[N], Cs[N], M, K, N)
+        fls.fls_dense_gemm(Wd, Xd[16], D, M, K, 16)
+    for rep in range(4):
+        for N in Xs:
+            Xs[N] = wl.gen_x(N, K, 60 + 7 * rep + N)
+            Xd[N].copy_(torch.from_numpy(Xs[N].view(np.float16)))
+            Cs[N].fill_(float("nan"))
+        D.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for N in Xs:
+            assert _rel_err(Cs[N].cpu().numpy(), oracle_mod.ref_spmm_f64(W, Xs[N])) <= TOL, (rep, N)
+        assert _rel_err(D.cpu().numpy(), oracle_mod.ref_spmm_f64(W, Xs[16])) <= TOL, rep
+        # eager work on the same workspace between replays
+        E = torch.full((16, M), float("nan"), dtype=torch.float16, device="cuda")
+        fls.fls_spmm(blob, Xd[16], E, M, K, 16)
+        torch.cuda.synchronize()
+        assert torch.equal(E, Cs[16])
+    ws = fls._ws_tensor
+    assert int(ws[512 * 4:512 * 4 + 4].cpu().numpy().view(np.uint32)[0]) == 0  # error word
+    assert int(ws[:512 * 4].cpu().numpy().view(np.uint32).max()) == 0  # every flag is down again
