@@ -247,8 +247,8 @@ int fls_dense_gemm(const void* W_dev, const void* X_dev, void* C_dev, int64_t M,
                    fls_stream_t stream) {
   int rc = check_mm_args(W_dev, X_dev, C_dev, M, K, N);
   if (rc != FLS_OK) return rc;
-  size_t need;
-  workspace_layout(K, N, &need, nullptr);
+  size_t need, xpack_offset;
+  workspace_layout(K, N, &need, &xpack_offset);
   void* ws;
   {
     std::lock_guard<std::mutex> lk(g_mu);
@@ -263,6 +263,7 @@ int fls_dense_gemm(const void* W_dev, const void* X_dev, void* C_dev, int64_t M,
   a.C = (_Float16*)C_dev;
   a.flags = (uint32_t*)ws;
   a.parts = (float*)((unsigned char*)ws + kCounterAreaBytes);
+  a.xpack = (_Float16*)((unsigned char*)ws + xpack_offset);
   a.M = (uint32_t)M;
   a.K = (uint32_t)K;
   a.N = (uint32_t)N;

@@ -150,6 +150,143 @@ static hipError_t launch_dense_variant(const DenseParams& p, int grid, hipStream
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- 64 columns per pass
+//
+// More than 32 columns: W is streamed once per 64 columns.  Four waves per workgroup, one per SIMD
+// with the whole register file (128 accumulator registers), each on its own row band; work is cut
+// as (group of four bands) x (K slice) as in the sparse kernel's 64-column pass, whose repacked X
+// (one coalesced 1 KB block per K tile and column block) and slice-adding kernel it shares.  No
+// LDS, no barrier, no waiting between workgroups.  A step covers 128 rows x 64 k: lane l reads 32
+// contiguous bytes of its row, so four lanes read a whole 128 B line, and the two MFMA K-steps of
+// a step take the first and the second 16 B; X follows the same assignment of k to lanes.
+#ifndef FLS_DENSE_WIDE_NS
+#define FLS_DENSE_WIDE_NS 2
+#endif
+
+template <int NS>
+__global__ __launch_bounds__(256) void dense_wide_kernel(WideParams p) {
+  constexpr int NB = 4;
+  const int lane = threadIdx.x & 63;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t group = blockIdx.x / p.S, slice = blockIdx.x - group * p.S;
+  const uint32_t band = group * 4 + wave;
+  if (band >= p.bands) return;
+  const uint32_t K = p.K, KT = p.KT;  // KT: steps of 64 k per band (the last one may be half)
+  const uint32_t s0 = (uint32_t)((uint64_t)slice * KT / p.S), s1 = (uint32_t)((uint64_t)(slice + 1) * KT / p.S);
+
+  float4v acc[kRowBlocks][NB];
+#pragma unroll
+  for (int rb = 0; rb < kRowBlocks; ++rb)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[rb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
+
+  const uint32_t g = lane >> 4, c = lane & 15;
+  const _Float16* wband = p.W + (size_t)band * kTileM * K;
+  const uint32_t lane_off = (c * K + g * 16u) * 2u, rb_step = 16u * K * 2u;
+  // X: K tile 2 s + (g >> 1) of step s; inside its block, the slot of k chunk 2 (g & 1) + h
+  const uint32_t ktiles = K / kTileK, xblocks = (p.N + 15u) / 16u;
+  const __amdgpu_buffer_rsrc_t xrsrc =
+      __builtin_amdgcn_make_buffer_rsrc((void*)p.Xp, 0, (int)(ktiles * xblocks * 1024u), kBufferFlags);
+  const uint32_t xlane = (p.n0 / 16u) * 1024u + ((2u * (g & 1u)) * 16u + c) * 16u;
+  const uint32_t xvalid = xblocks - p.n0 / 16u;  // column blocks left from n0 on: the others read as zero
+  // a half last step (K = 64 j + 32): the lanes of its upper 32 k drop out
+  const bool half_last = (K & 63u) != 0;
+  const bool upper = g >= 2;
+
+  uint32_t si = s0;  // next step to request
+  auto issue = [&](half8(&a)[kRowBlocks][2], half8(&x)[NB][2]) {
+    // past the slice: an empty descriptor, loads return 0 and move no data
+    const uint32_t kleft = K - si * 64u;
+    const uint32_t span = (127u * K + (kleft < 64u ? kleft : 64u)) * 2u;
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)(wband + (size_t)si * 64u), 0, si < s1 ? (int)span : 0, kBufferFlags);
+#pragma unroll
+    for (int rb = 0; rb < kRowBlocks; ++rb)
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+        a[rb][h] = __builtin_bit_cast(
+            half8, __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane_off + rb * rb_step + h * 16, 0, kAuxNonTemporal));
+    const uint32_t kt = 2u * si + (g >> 1);
+    const bool live = si < s1 && kt < ktiles;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+        x[nb][h] = __builtin_bit_cast(
+            half8, __builtin_amdgcn_raw_buffer_load_b128(
+                       xrsrc, live && (uint32_t)nb < xvalid ? kt * xblocks * 1024u + xlane + nb * 1024u + h * 256u : 0xffffff00u, 0, 0));
+    ++si;
+  };
+
+  half8 a[NS][kRowBlocks][2], x[NS][NB][2];
+#pragma unroll
+  for (int i = 0; i < NS; ++i) issue(a[i], x[i]);
+  uint32_t sc = s0;
+  auto step = [&](half8(&sa)[kRowBlocks][2], half8(&sx)[NB][2]) {
+    if (half_last && sc + 1 == KT && upper) {
+      // k past the end of the row: X read as zero there, W must not bring Inf or NaN either
+      const half8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int rb = 0; rb < kRowBlocks; ++rb)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) sa[rb][h] = z;
+    }
+#pragma unroll
+    for (int rb = 0; rb < kRowBlocks; ++rb)
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+          acc[rb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(sa[rb][h], sx[nb][h], acc[rb][nb], 0, 0, 0);
+    issue(sa, sx);
+    ++sc;
+  };
+  while (sc + NS <= s1) {
+#pragma unroll
+    for (int i = 0; i < NS; ++i) step(a[i], x[i]);
+  }
+#pragma unroll
+  for (int i = 0; i < NS - 1; ++i)
+    if (sc < s1) step(a[i], x[i]);
+
+  if (p.S == 1) {
+    OutParams o;
+    o.C = p.C;
+    o.M = p.M;
+    o.N = p.N;
+    o.n0 = p.n0;
+    store_band<NB>(o, acc, band, lane);
+  } else {
+    float4v* dst = (float4v*)p.parts + ((size_t)(band * p.S + slice) * (NB * kRowBlocks)) * 64 + lane;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int rb = 0; rb < kRowBlocks; ++rb) dst[(nb * kRowBlocks + rb) * 64] = acc[rb][nb];
+  }
+}
+
+static hipError_t launch_dense_wide(const DenseLaunch& a, uint32_t n0, hipStream_t stream) {
+  WideParams p;
+  p.offs = nullptr;
+  p.words = nullptr;
+  p.W = a.W;
+  p.Xp = a.xpack;
+  p.C = a.C;
+  p.parts = a.parts;
+  p.M = a.M;
+  p.K = a.K;
+  p.N = a.N;
+  p.n0 = n0;
+  p.KT = (a.K + 63u) / 64u;
+  p.bands = a.M / kTileM;
+  p.S = wide_slices(p.bands, p.KT, a.num_cus);
+  const uint32_t groups = (p.bands + 3u) / 4u;
+  hipLaunchKernelGGL((dense_wide_kernel<FLS_DENSE_WIDE_NS>), dim3(groups * p.S), dim3(256), 0, stream, p);
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess && p.S > 1) e = launch_wide_reduce(p, stream);
+  return e;
+}
+
 hipError_t launch_dense(const DenseLaunch& a, hipStream_t stream) {
   DenseParams p;
   p.W = a.W;
@@ -161,15 +298,25 @@ hipError_t launch_dense(const DenseLaunch& a, hipStream_t stream) {
   p.out.M = a.M;
   p.out.N = a.N;
   const int grid = pick_grid(a.M / kTileM, a.K / kTileK, a.num_cus);
-  for (uint32_t n0 = 0; n0 < a.N; n0 += kGroupCols) {
+  if (a.N > kGroupCols) {
+    hipError_t e = launch_xpack(a.X, a.xpack, a.K, a.N, stream);  // the 64-column passes read X in fragment order
+    if (e != hipSuccess) return e;
+  }
+  for (uint32_t n0 = 0; n0 < a.N;) {
     p.out.n0 = n0;
-    const uint32_t ncols = a.N - n0 < kGroupCols ? a.N - n0 : kGroupCols;
+    const uint32_t left = a.N - n0;
     hipError_t e;
-    const uint32_t h = ncols <= 16 ? 2 : 1;
-    p.out.KT = (a.K + 32 * h - 1) / (32 * h);
-    p.out.T = (a.M / kTileM) * p.out.KT;
-    if (ncols <= 16) e = launch_dense_variant<1, 8, 2, 2>(p, grid, stream);
-    else e = launch_dense_variant<2, 8, 2, 1>(p, grid, stream);
+    if (left > kGroupCols) {
+      e = launch_dense_wide(a, n0, stream);
+      n0 += kSpmmGroupCols;
+    } else {
+      const uint32_t h = left <= 16 ? 2 : 1;
+      p.out.KT = (a.K + 32 * h - 1) / (32 * h);
+      p.out.T = (a.M / kTileM) * p.out.KT;
+      if (left <= 16) e = launch_dense_variant<1, 8, 2, 2>(p, grid, stream);
+      else e = launch_dense_variant<2, 8, 2, 1>(p, grid, stream);
+      n0 += kGroupCols;
+    }
     if (e != hipSuccess) return e;
   }
   return hipSuccess;

@@ -237,7 +237,7 @@ __device__ __forceinline__ void owner_finish(const OutParams& o, float4v (&acc)[
   // As many loads as the registers allow are issued before the first is used: each is a trip
   // to memory, and this runs when the kernel is about to end, with nothing left to hide it behind.
   constexpr int kBatch = NB == 1 ? 4 : 2;  // slots in flight
-  constexpr int kBlocks = NB;               // column blocks of a slot in flight
+  constexpr int kBlocks = NB > 2 ? 2 : NB;  // column blocks of a slot in flight
   uint32_t q = wg + 1;
   while (q < P && share_begin(q, o.T, P) < band_hi) {
     __amdgpu_buffer_rsrc_t src[kBatch];

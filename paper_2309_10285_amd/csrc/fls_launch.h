@@ -24,6 +24,7 @@ struct DenseLaunch {
   _Float16* C;
   float* parts;
   uint32_t* flags;
+  _Float16* xpack;  // as in SpmmLaunch
   uint32_t M, K, N;
   int num_cus;
 };
@@ -87,10 +88,23 @@ inline int pick_grid(uint32_t bands, uint32_t tiles_per_band, int cus) {
   return cus;
 }
 
+// Arguments of the 64-column passes (sparse and dense) and of the kernel that adds their K slices.
+struct WideParams {
+  const uint32_t* offs;   // TileOffsets (sparse pass)
+  const uint32_t* words;  // NonZeros (sparse pass)
+  const _Float16* W;      // dense matrix (dense pass)
+  const _Float16* Xp;     // X in fragment order: [K tile][column block of all N][lane][8 halves]
+  _Float16* C;
+  float* parts;           // [band][slice][column block][row block][lane] float4, used when S > 1
+  uint32_t M, K, N, n0, KT, bands, S;
+};
+
 hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream);
-// X -> a.xpack (fragment order), then one 64-column pass per call of launch_spmm_wide from column n0 on
-hipError_t launch_xpack(const SpmmLaunch& a, hipStream_t stream);
+// X -> xpack (fragment order, all N columns), then one 64-column pass per call of launch_spmm_wide from column n0 on
+hipError_t launch_xpack(const _Float16* X, _Float16* xpack, uint32_t K, uint32_t N, hipStream_t stream);
 hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, hipStream_t stream);
+// C = sum over the S slices of parts, in slice order (the second kernel of a 64-column pass with S > 1)
+hipError_t launch_wide_reduce(const WideParams& p, hipStream_t stream);
 hipError_t launch_dense(const DenseLaunch& a, hipStream_t stream);
 // phase 1: per-tile counts, prefix sums, header (everything but the words)
 hipError_t launch_compress_index(const CompressLaunch& a, hipStream_t stream);

@@ -389,7 +389,7 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
   // matrix with denser tiles - less than half sparse somewhere - takes 32-column passes throughout.
   const bool wide_ok = a.max_tile_words <= 8 * 256;
   if (a.N > kGroupCols && wide_ok) {
-    hipError_t e = launch_xpack(a, stream);  // the 64-column passes read X from a copy in fragment order
+    hipError_t e = launch_xpack(a.X, a.xpack, a.K, a.N, stream);  // the 64-column passes read X from a copy in fragment order
     if (e != hipSuccess) return e;
   }
   for (uint32_t n0 = 0; n0 < a.N;) {

@@ -31,15 +31,6 @@ constexpr int kXTileBytes = kWideNB * 1024;     // one K tile of X for 64 column
 constexpr int kXChunkBytes = kWideWaves * kXTileBytes;
 constexpr int kWideLdsBytes = kWideWaves * kWideTileLds + 2 * kXChunkBytes;
 
-struct WideParams {
-  const uint32_t* offs;   // TileOffsets
-  const uint32_t* words;  // NonZeros
-  const _Float16* Xp;     // X in fragment order: [K tile][column block of all N][lane][8 halves]
-  _Float16* C;
-  float* parts;           // [band][slice][column block][row block][lane] float4, used when S > 1
-  uint32_t M, N, n0, KT, bands, S;
-};
-
 // X in MFMA fragment order: block (K tile kt, column block nb) holds, for lane l = 16 g + c, the 8
 // halves X[32 kt + 8 g .. +7][16 nb + c] (zeros for columns past N).  One wave per block; loads are
 // quad-contiguous (lane j reads column j >> 2, chunk j & 3), stores go to the fragment position.
@@ -334,9 +325,15 @@ static hipError_t launch_wide_variant(const WideParams& p, int grid, hipStream_t
 }
 
 // X (all N columns of the call) into fragment order, once per call.
-hipError_t launch_xpack(const SpmmLaunch& a, hipStream_t stream) {
-  const uint32_t blocks = (a.N + 15u) / 16u, units = (a.K / kTileK) * blocks;
-  hipLaunchKernelGGL(xpack_kernel, dim3((units + 3) / 4), dim3(256), 0, stream, a.X, a.xpack, a.K, a.N, units, blocks);
+hipError_t launch_xpack(const _Float16* X, _Float16* xpack, uint32_t K, uint32_t N, hipStream_t stream) {
+  const uint32_t blocks = (N + 15u) / 16u, units = (K / kTileK) * blocks;
+  hipLaunchKernelGGL(xpack_kernel, dim3((units + 3) / 4), dim3(256), 0, stream, X, xpack, K, N, units, blocks);
+  return hipGetLastError();
+}
+
+hipError_t launch_wide_reduce(const WideParams& p, hipStream_t stream) {
+  const uint32_t units = p.bands * (kWideNB * kRowBlocks);
+  hipLaunchKernelGGL(wide_reduce_kernel, dim3((units + 3) / 4), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 
@@ -345,10 +342,12 @@ hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, hipStream_t stream
   WideParams p;
   p.offs = a.offs;
   p.words = a.words;
+  p.W = nullptr;
   p.Xp = a.xpack;
   p.C = a.C;
   p.parts = a.parts;
   p.M = a.M;
+  p.K = a.K;
   p.N = a.N;
   p.n0 = n0;
   p.KT = a.K / kTileK;
@@ -363,11 +362,7 @@ hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, hipStream_t stream
   else if (a.max_tile_words <= 6 * 256) e = launch_wide_variant<6, 4>(p, grid, stream);
   else e = launch_wide_variant<8, 4>(p, grid, stream);
   if (e != hipSuccess) return e;
-  if (p.S > 1) {
-    const uint32_t units = p.bands * (kWideNB * kRowBlocks);
-    hipLaunchKernelGGL(wide_reduce_kernel, dim3((units + 3) / 4), dim3(256), 0, stream, p);
-    e = hipGetLastError();
-  }
+  if (p.S > 1) e = launch_wide_reduce(p, stream);
   return e;
 }
 
