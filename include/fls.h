@@ -45,7 +45,9 @@ enum {
   FLS_ECAPACITY = -3,  /* output buffer too small; stats->bytes_total holds the size needed */
   FLS_EFORMAT = -4,    /* blob header: bad magic / version / geometry, or M, K differ from the call */
   FLS_EWORKSPACE = -5, /* no workspace registered, or it is too small for this call */
-  FLS_EHIP = -6        /* a HIP call failed (the HIP error stays readable with hipGetLastError) */
+  FLS_EHIP = -6,       /* a HIP call failed (the HIP error stays readable with hipGetLastError) */
+  FLS_EHANDOVER = -7   /* a kernel gave up waiting for another workgroup's partial sum: results of the calls
+                          since the last check are not to be trusted (fls_check_workspace) */
 };
 
 /* opaque stream handle: pass a hipStream_t (NULL = the default stream) */
@@ -119,13 +121,22 @@ size_t fls_workspace_bytes(int64_t M, int64_t K, int64_t N);
 int fls_set_workspace(void* ws_dev, size_t bytes, fls_stream_t stream);
 
 /*
+ * Waits for `stream` and reads the workspace's error word.  The split-K hand-over (Alg. 1 has
+ * none: a thread block there walks the whole K) makes one workgroup wait for the partial sums of
+ * others; that wait is bounded (about a second), and a kernel that gives up says so here instead
+ * of hanging.  Returns FLS_OK, or FLS_EHANDOVER after clearing the control area again so that
+ * later calls start clean; FLS_EWORKSPACE if none is registered; FLS_EHIP.
+ */
+int fls_check_workspace(fls_stream_t stream);
+
+/*
  * C = W . X with W given as a Tiled-CSL blob (the SpMM of Alg. 1): streams the blob from HBM
  * (once per 64 columns for N > 32, else once), rebuilds each tile densely in LDS, multiplies
  * with MFMA, fp32 accumulation.  The result does not depend on timing: partial sums are added
  * in a fixed order.  2*K*N and 2*M*N must stay below 2^31 (32-bit byte offsets into X and C).
  *   Wc_dev in : blob made by fls_compress (or byte-identical); its header must match M, K
  *   X_dev  in : fp16 column-major K x N;  C_dev out: fp16 column-major M x N (fully overwritten)
- * The first call on a given blob address reads its 64-byte header back (a blocking copy) to
+ * The first call on a given blob address reads its 64-byte header back (a copy on `stream`, waited for) to
  * validate it and to pick the kernel variant; later calls on that address do not.  Call
  * fls_forget when the memory at that address comes to hold a different blob by other means than
  * fls_compress (a copy, a freed buffer handed out again).  A remembered header that is out of date

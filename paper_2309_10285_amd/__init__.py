@@ -17,7 +17,7 @@ MAX_N = 256
 ORDER_LOCATION = 0
 ORDER_BANK = 1
 
-OK, EINVAL, EALIGN, ECAPACITY, EFORMAT, EWORKSPACE, EHIP = 0, -1, -2, -3, -4, -5, -6
+OK, EINVAL, EALIGN, ECAPACITY, EFORMAT, EWORKSPACE, EHIP, EHANDOVER = 0, -1, -2, -3, -4, -5, -6, -7
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfls.so")
@@ -25,7 +25,7 @@ _lib = None
 _ws_tensor = None  # keeps the registered workspace alive
 
 EXPORTS = ("fls_compress_bound", "fls_compress", "fls_inspect", "fls_workspace_bytes", "fls_set_workspace",
-           "fls_spmm", "fls_forget", "fls_dense_gemm", "fls_strerror")
+           "fls_check_workspace", "fls_spmm", "fls_forget", "fls_dense_gemm", "fls_strerror")
 
 
 class FlsStats(ctypes.Structure):
@@ -63,6 +63,8 @@ def lib():
         L.fls_workspace_bytes.restype = sz
         L.fls_set_workspace.argtypes = [vp, sz, vp]
         L.fls_set_workspace.restype = ci
+        L.fls_check_workspace.argtypes = [vp]
+        L.fls_check_workspace.restype = ci
         L.fls_spmm.argtypes = [vp, vp, vp, i64, i64, i64, vp]
         L.fls_spmm.restype = ci
         L.fls_forget.argtypes = [vp]
@@ -193,6 +195,11 @@ def prepare_dense_gemm(W, X, C, M, K, N):
             _check(rc, "fls_dense_gemm")
 
     return call
+
+
+def fls_check_workspace():
+    """Waits for the current stream; raises FlsError(EHANDOVER) if a kernel gave up on a split-K hand-over."""
+    _check(lib().fls_check_workspace(_stream()), "fls_check_workspace")
 
 
 def fls_forget(blob=None):

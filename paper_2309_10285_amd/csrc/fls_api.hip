@@ -189,6 +189,24 @@ int fls_set_workspace(void* ws_dev, size_t bytes, fls_stream_t stream) {
   return FLS_OK;
 }
 
+int fls_check_workspace(fls_stream_t stream) {
+  void* ws;
+  {
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!g_ws || g_ws_bytes < kCounterAreaBytes) return FLS_EWORKSPACE;
+    ws = g_ws;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  uint32_t word = 0;
+  if (hipMemcpyAsync(&word, (const uint32_t*)ws + fls::kMaxWorkgroups, sizeof(word), hipMemcpyDeviceToHost, s) != hipSuccess)
+    return FLS_EHIP;
+  if (hipStreamSynchronize(s) != hipSuccess) return FLS_EHIP;
+  if (word == 0) return FLS_OK;
+  // flags of the launch that gave up may have stayed up
+  if (fls::launch_fill_zero(ws, kCounterAreaBytes, s) != hipSuccess) return FLS_EHIP;
+  return FLS_EHANDOVER;
+}
+
 void fls_forget(const void* Wc_dev) {
   std::lock_guard<std::mutex> lk(g_mu);
   if (Wc_dev) g_blobs.erase(Wc_dev);
@@ -214,8 +232,10 @@ int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int6
   }
   if (!known || info.M != (uint64_t)M || info.K != (uint64_t)K) {
     // unknown address, or the memory now holds another blob than the one remembered: read the header
+    // on the call's stream: the blob may have been put there by work still queued on it
     unsigned char hdr[FLS_HEADER_BYTES];
-    if (hipMemcpy(hdr, Wc_dev, FLS_HEADER_BYTES, hipMemcpyDeviceToHost) != hipSuccess) return FLS_EHIP;
+    if (hipMemcpyAsync(hdr, Wc_dev, FLS_HEADER_BYTES, hipMemcpyDeviceToHost, (hipStream_t)stream) != hipSuccess) return FLS_EHIP;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return FLS_EHIP;
     rc = parse_header(hdr, nullptr, &info);
     std::lock_guard<std::mutex> lk(g_mu);
     if (rc != FLS_OK) {
@@ -280,6 +300,7 @@ const char* fls_strerror(int code) {
     case FLS_EFORMAT: return "compressed blob header is malformed or does not match M, K";
     case FLS_EWORKSPACE: return "workspace missing or too small (see fls_workspace_bytes / fls_set_workspace)";
     case FLS_EHIP: return "a HIP runtime call failed";
+    case FLS_EHANDOVER: return "a kernel gave up waiting for another workgroup's partial sum; results since the last check are not to be trusted";
     default: return "unknown error code";
   }
 }

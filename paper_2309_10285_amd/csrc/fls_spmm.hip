@@ -359,6 +359,7 @@ template <int NB, int WAVES>
 static hipError_t launch_r(int R, const SpmmParams& p, int grid, hipStream_t stream) {
   switch (R) {
     case 2: return launch_variant<NB, WAVES, 2>(p, grid, stream);
+    case 3: return launch_variant<NB, WAVES, 3>(p, grid, stream);
     case 4: return launch_variant<NB, WAVES, 4>(p, grid, stream);
     case 6: return launch_variant<NB, WAVES, 6>(p, grid, stream);
     default: return launch_variant<NB, WAVES, 8>(p, grid, stream);
@@ -383,6 +384,7 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
   // (a denser tile is still handled, through a slow path)
   int R = 8;
   if (a.max_tile_words <= 2 * 256) R = 2;
+  else if (a.max_tile_words <= 3 * 256) R = 3;
   else if (a.max_tile_words <= 4 * 256) R = 4;
   else if (a.max_tile_words <= 6 * 256) R = 6;
   // The 64-column pass stages at most 2048 words of a tile (it has no slow path for more): a

@@ -358,6 +358,7 @@ hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, hipStream_t stream
   hipError_t e;
   // rounds of 256 words staged per tile; the ring is 8 tiles deep while the registers allow
   if (a.max_tile_words <= 2 * 256) e = launch_wide_variant<2, 8>(p, grid, stream);
+  else if (a.max_tile_words <= 3 * 256) e = launch_wide_variant<3, 8>(p, grid, stream);
   else if (a.max_tile_words <= 4 * 256) e = launch_wide_variant<4, 8>(p, grid, stream);
   else if (a.max_tile_words <= 6 * 256) e = launch_wide_variant<6, 4>(p, grid, stream);
   else e = launch_wide_variant<8, 4>(p, grid, stream);

@@ -56,6 +56,7 @@ def test_argument_errors_need_no_device(fls):
     assert L.fls_spmm(16, 8, 16, 128, 32, 8, None) == fls.EALIGN
     assert L.fls_spmm(16, 16, 16, 128, 32, 8, None) == fls.EWORKSPACE   # nothing registered
     assert L.fls_dense_gemm(16, 16, 16, 128, 32, 8, None) == fls.EWORKSPACE
+    assert L.fls_check_workspace(None) == fls.EWORKSPACE
     assert L.fls_dense_gemm(None, 16, 16, 128, 32, 8, None) == fls.EINVAL
     assert L.fls_compress(None, 128, 32, 16, 1 << 20, 0, None, None) == fls.EINVAL
     assert L.fls_compress(16, 128, 32, 16, 1 << 20, 7, None, None) == fls.EINVAL

@@ -79,6 +79,9 @@ def _cases():
         ("long-share-kt1", 128 * 2304, 32, 0.8, "uniform"),
         ("long-share-kt2", 128 * 1500, 64, 0.8, "uniform"),
         ("long-share-kt3", 128 * 1111, 96, 0.7, "uniform"),
+        # longest tile between 512 and 768 words, and between 1024 and 1536: the three- and six-round rings
+        ("uniform-87", 1024, 1024, 0.87, "uniform"),
+        ("uniform-68", 768, 1024, 0.68, "uniform"),
     ]:
         W32 = wl.gen_weights_f32(M, K, int(g.integers(1 << 30)))
         if mask == "uniform":
@@ -214,7 +217,7 @@ def test_spmm_order_invariance(fls, oracle_mod):
     assert _rel_err(C.cpu().numpy(), ref) <= TOL
 
 
-@pytest.mark.parametrize("name,W", CASES[:6] + CASES[9:], ids=[c[0] for c in CASES[:6] + CASES[9:]])
+@pytest.mark.parametrize("name,W", CASES[:6] + CASES[9:12], ids=[c[0] for c in CASES[:6] + CASES[9:12]])
 @pytest.mark.parametrize("N", [8, 16, 40, 64, 256])
 def test_dense_gemm_matches_oracle(fls, oracle_mod, name, W, N):
     M, K = W.shape
@@ -311,7 +314,7 @@ def test_back_to_back_shapes_share_one_workspace(fls, oracle_mod):
             assert _rel_err(C.cpu().numpy(), ref) <= TOL
             assert _rel_err(D.cpu().numpy(), ref) <= TOL
     assert fls._ws_tensor is ws  # still the same registration
-    assert int(ws[512 * 4:512 * 4 + 4].cpu().numpy().view(np.uint32)[0]) == 0  # error word: flags[512]
+    fls.fls_check_workspace()  # raises if a hand-over wait gave up
 
 
 def test_very_long_k(fls, oracle_mod):
@@ -400,6 +403,29 @@ def test_calls_recorded_in_a_graph_replay_right(fls, oracle_mod):
         fls.fls_spmm(blob, Xd[16], E, M, K, 16)
         torch.cuda.synchronize()
         assert torch.equal(E, Cs[16])
-    ws = fls._ws_tensor
-    assert int(ws[512 * 4:512 * 4 + 4].cpu().numpy().view(np.uint32)[0]) == 0  # error word
-    assert int(ws[:512 * 4].cpu().numpy().view(np.uint32).max()) == 0  # every flag is down again
+    fls.fls_check_workspace()  # raises if a hand-over wait gave up
+    assert int(fls._ws_tensor[:512 * 4].cpu().numpy().view(np.uint32).max()) == 0  # every flag is down again
+
+
+def test_check_workspace_reports_a_hand_over_that_gave_up(fls, oracle_mod):
+    """The error word a kernel would set after its bounded wait is planted from the host (no kernel is made to
+    wait): fls_check_workspace reports it once, clears the control area, and the next calls run clean."""
+    import torch
+
+    name, W = CASES[1]
+    M, K = W.shape
+    X = wl.gen_x(16, K, 71)
+    fls.ensure_workspace(M, K, 16)
+    fls.fls_check_workspace()
+    ws32 = fls._ws_tensor[:4 << 20].view(torch.int32)
+    ws32[512] = 1  # the error word
+    ws32[3] = 1    # and a flag left up, as the launch that gave up would leave it
+    torch.cuda.synchronize()
+    with pytest.raises(fls.FlsError) as e:
+        fls.fls_check_workspace()
+    assert e.value.code == fls.EHANDOVER
+    fls.fls_check_workspace()
+    assert int(ws32[:513].abs().max()) == 0
+    _, _, C = _run_spmm(fls, W, X, 16)
+    assert _rel_err(C, oracle_mod.ref_spmm_f64(W, X)) <= TOL
+    fls.fls_check_workspace()
