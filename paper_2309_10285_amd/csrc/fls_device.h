@@ -39,6 +39,14 @@ constexpr int kBufferFlags = 0x00020000;    // raw buffer, 32-bit data format (g
 constexpr int kAuxNonTemporal = 2;          // nt: streamed once, do not keep in the caches
 constexpr int kAuxCoherent = 16;            // sc1: device scope - through to memory / past the per-XCD L2
 
+// LDS byte address a word of a tile goes to: base + 2 * location (the word's low half), in one
+// instruction (v_mad_u32_u16: D = S0.u16 * S1.u16 + S2.u32).
+__device__ __forceinline__ uint32_t scatter_addr(uint32_t word, uint32_t base) {
+  uint32_t addr;
+  asm("v_mad_u32_u16 %0, %1, 2, %2" : "=v"(addr) : "v"(word), "v"(base));
+  return addr;
+}
+
 // What both kernels need to hand results over.
 //
 // Split-K: the band-major tile sequence [0, T) is cut evenly over the workgroups, then over the

@@ -127,7 +127,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const uint32_t w = s[r][j];
-          const uint32_t addr = tile_addr + ((w & 0xffffu) << 1);
+          const uint32_t addr = scatter_addr(w, tile_addr);
           if (FLS_ABLATE & 4) asm volatile("" ::"v"(w));
           else *(lds_u16_ptr)(uintptr_t)addr = (uint16_t)(w >> 16);
           s[r][j] = addr;

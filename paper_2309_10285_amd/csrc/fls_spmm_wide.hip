@@ -128,8 +128,9 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   };
 
   // extract (Alg. 2), branch-free so that a step is one basic block: lanes past the end of the
-  // run (their loads returned 0) are pointed at the slot that padding words go to.  The words are
-  // then replaced by the LDS addresses they went to, which is all the later re-zeroing needs.
+  // run (their loads returned 0: location 0, value 0) get the slot that padding words go to as
+  // their base.  The words are then replaced by the LDS addresses they went to, which is all the
+  // later re-zeroing needs.
   // (No tile has more than R * 256 words here: see `densest` below.)
   typedef __attribute__((address_space(3))) uint16_t* lds_u16_ptr;
   const uint32_t tile_addr = (uint32_t)(uintptr_t)tile;  // LDS addresses are the low 32 bits
@@ -137,11 +138,11 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
     const uint32_t n = end - begin;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      const bool valid = (r * 64 + lane) * 4u < n;
+      const uint32_t base = (r * 64 + lane) * 4u < n ? tile_addr : tile_addr + (uint32_t)kTileBytes;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const uint32_t w = valid ? s[r][j] : (uint32_t)kTileElems;
-        const uint32_t addr = tile_addr + ((w & 0xffffu) << 1);
+        const uint32_t w = s[r][j];
+        const uint32_t addr = scatter_addr(w, base);
         *(lds_u16_ptr)(uintptr_t)addr = (uint16_t)(w >> 16);
         s[r][j] = addr;
       }
