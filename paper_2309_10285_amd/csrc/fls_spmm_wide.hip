@@ -1,14 +1,16 @@
 // fls_spmm for more than 32 columns: 64 columns per pass (Flash-LLM's kernel for its widest batch
 // sizes, re-cut for gfx950).
 //
-// With 64 columns a tile needs 4 KB of X against some 1.6 - 5 KB of compressed W, and a CU's
-// vector-memory path moves only a few tens of bytes per clock, so re-reading X from L2 for every
-// row band bounds the kernel long before HBM or the MFMAs do.  Here X goes through LDS instead and
-// is shared: a workgroup has four waves, each on its own row band (four consecutive bands, one
-// wave per SIMD with the whole register file: 128 accumulator registers and a deep load ring),
-// all four walking the same K range tile by tile.  Every wave fetches one of every four X tiles
-// and puts it into LDS for all of them (double-buffered chunks of four tiles, one workgroup
-// barrier per chunk), which cuts the X traffic of a CU by four.
+// A workgroup has four waves, one per SIMD with the whole register file (128 accumulator
+// registers, a deep ring of tiles in flight), each on its own row band; the waves share nothing
+// but the CU: no barrier, no waiting.  With 64 columns a tile needs 4 KB of X against some
+// 1.6 - 5 KB of compressed W, so how X reaches the MFMAs matters as much as W: a first kernel
+// repacks X once per call into MFMA fragment order, after which a wave's four B fragments of a K
+// tile are four fully coalesced 1 KB loads from L2, kept a few tiles ahead in a register ring of
+// their own.  (Fragments loaded from X as the caller lays it out touch sixteen cache lines per
+// load and bound the kernel; X shared between the four waves through LDS - double-buffered
+// chunks, one barrier per four tiles - costs LDS bandwidth and lockstep, and measured 6 - 10 %
+// slower for sparse tiles.)
 //
 // Work is cut as (group of four bands) x (K slice): S slices per group so that the grid fills
 // the CUs.  A wave's accumulators are its band's partial result for its slice: with S = 1 they are
@@ -24,12 +26,10 @@
 
 namespace fls {
 
-constexpr int kWideWaves = 4;                   // = bands per group = X tiles per chunk
+constexpr int kWideWaves = 4;                   // = bands per group
 constexpr int kWideNB = 4;                      // column blocks per pass
 constexpr int kWideTileLds = kTileBytes + 16;   // a wave's tile + the slot padding words land in
-constexpr int kXTileBytes = kWideNB * 1024;     // one K tile of X for 64 columns, in fragment order
-constexpr int kXChunkBytes = kWideWaves * kXTileBytes;
-constexpr int kWideLdsBytes = kWideWaves * kWideTileLds + 2 * kXChunkBytes;
+constexpr int kWideLdsBytes = kWideWaves * kWideTileLds;
 
 // X in MFMA fragment order: block (K tile kt, column block nb) holds, for lane l = 16 g + c, the 8
 // halves X[32 kt + 8 g .. +7][16 nb + c] (zeros for columns past N).  One wave per block; loads are
@@ -47,25 +47,22 @@ __global__ __launch_bounds__(256) void xpack_kernel(const _Float16* X, _Float16*
   *(u32x4*)(Xp + ((size_t)u * 64u + g * 16u + c) * 8u) = v;
 }
 
-template <int R, int NS>
+template <int R, int NS, int XS>
 __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p) {
   constexpr int NB = kWideNB;
-  static_assert(NS % kWideWaves == 0, "the unrolled ring must hold whole X chunks");
+  static_assert(NS % XS == 0, "the unrolled ring must hold whole turns of the X ring");
   extern __shared__ __align__(16) unsigned char lds[];
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t group = blockIdx.x / p.S, slice = blockIdx.x - group * p.S;
   const uint32_t band = group * kWideWaves + wave;
+  if (band >= p.bands) return;  // the waves of a workgroup share nothing but the CU
   const uint32_t KT = p.KT, T = p.bands * KT;
   const uint32_t k0 = (uint32_t)((uint64_t)slice * KT / p.S), k1 = (uint32_t)((uint64_t)(slice + 1) * KT / p.S);
-  // a wave past the last band walks an empty run: it still fetches its share of X and meets the barriers
-  const bool active = band < p.bands;
-  const uint32_t t0 = active ? band * KT + k0 : T, t1 = active ? band * KT + k1 : T;
-  // bodies of NS steps; every wave of the workgroup runs the same number of them
-  const uint32_t bodies = (k1 - k0 + NS - 1) / NS;
+  const uint32_t t0 = band * KT + k0, t1 = band * KT + k1;
+  const uint32_t bodies = (k1 - k0 + NS - 1) / NS;  // of NS steps each
 
   unsigned char* tile = lds + wave * kWideTileLds;
-  unsigned char* xbuf = lds + kWideWaves * kWideTileLds;
   const u32x4 zero4 = {0u, 0u, 0u, 0u};
 #pragma unroll
   for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
@@ -83,22 +80,19 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   const uint32_t xlane = (p.n0 / 16u) * 1024u + (uint32_t)lane * 16u;
   // the last pass of a call may have fewer than four column blocks left: the others read as zero
   const uint32_t xvalid = xblocks - p.n0 / 16u;
-  // (everything that may leave the buffer is in the per-lane offset: that is the part the
-  // bounds check of a raw buffer looks at)
-  auto xload = [&](u32x4(&xr)[NB], uint32_t chunk) {
-    const uint32_t kt = k0 + chunk * kWideWaves + wave;
-    // tiles past the slice (the padding of the last body) must contribute nothing even if X holds
-    // Inf or NaN further along K: their X reads as zero
-    const uint32_t base = kt * xblocks * 1024u + xlane;
+  // One tile's four blocks into a stage of the X ring.  Tiles past the slice (the padding of the
+  // last body) must contribute nothing even if X holds Inf or NaN further along K: their X reads
+  // as zero.  (Everything that may leave the buffer is in the per-lane offset: that is the part
+  // the bounds check of a raw buffer looks at.)
+  uint32_t xti = k0;
+  auto xissue = [&](u32x4(&xq)[NB]) {
+    const uint32_t base = xti * xblocks * 1024u + xlane;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      const bool wanted = kt < k1 && (uint32_t)nb < xvalid;
-      xr[nb] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, wanted ? base + nb * 1024u : 0xffffff00u, 0, 0);  // else: 0
+      const bool wanted = xti < k1 && (uint32_t)nb < xvalid;
+      xq[nb] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, wanted ? base + nb * 1024u : 0xffffff00u, 0, 0);  // else: 0
     }
-  };
-  auto xstore = [&](const u32x4(&xr)[NB], uint32_t buf) {
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) *(u32x4*)(xbuf + buf * kXChunkBytes + wave * kXTileBytes + nb * 1024 + lane * 16) = xr[nb];
+    ++xti;
   };
 
   // TileOffsets: a window of 64 entries in a VGPR (lane i = entry base + i), replaced once per
@@ -130,8 +124,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   // extract (Alg. 2), branch-free so that a step is one basic block: lanes past the end of the
   // run (their loads returned 0: location 0, value 0) get the slot that padding words go to as
   // their base.  The words are then replaced by the LDS addresses they went to, which is all the
-  // later re-zeroing needs.
-  // (No tile has more than R * 256 words here: see `densest` below.)
+  // later re-zeroing needs.  (No tile has more than R * 256 words here: see `densest` below.)
   typedef __attribute__((address_space(3))) uint16_t* lds_u16_ptr;
   const uint32_t tile_addr = (uint32_t)(uintptr_t)tile;  // LDS addresses are the low 32 bits
   auto extract = [&](u32x4(&s)[R], uint32_t begin, uint32_t end) {
@@ -150,9 +143,6 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   };
 
   const unsigned char* frag = tile + ((lane >> 4) * kTileM + (lane & 15)) * 16;
-  u32x4 s[NS][R];
-  uint32_t sb[NS], se[NS];
-  u32x4 xr[NB];
 
   // rst_smem.  Sparse tiles (R <= 4: at most 1024 words) are re-zeroed by storing zeros where
   // their words went - as many 2 B stores as the extraction - instead of clearing all 8 KB.
@@ -164,15 +154,16 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
       for (int j = 0; j < 4; ++j) *(lds_u16_ptr)(uintptr_t)s[r][j] = (uint16_t)0;
   };
 
-  // One tile, whose words stage `cur` still holds and which the step before extracted into LDS:
-  // its fragments are read (A from the wave's tile, B from the X chunk), the tile is re-zeroed
-  // behind the reads, stage `cur` is refilled, the next tile (stage `nxt`) is extracted, and the
-  // MFMAs run spread between those instructions.
+  // One tile, whose words stage `cur` still holds (as LDS addresses by now) and which the step
+  // before extracted into LDS: the X stage that step used is refilled, the tile's A fragments are
+  // read, the tile is re-zeroed behind the reads, stage `cur` is refilled, the next tile (stage
+  // `nxt`) is extracted, and the MFMAs run spread between those instructions.
   auto step = [&](u32x4(&cur)[R], uint32_t& cb, uint32_t& ce, u32x4(&nxt)[R], uint32_t nb_, uint32_t ne_,
-                  const unsigned char* xt) {
+                  u32x4(&xfill)[NB], const u32x4(&xuse)[NB]) {
     half8 fa[kRowBlocks], fb[NB];
+    xissue(xfill);
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) fb[nb] = *(const half8*)(xt + nb * 1024 + lane * 16);
+    for (int nb = 0; nb < NB; ++nb) fb[nb] = __builtin_bit_cast(half8, xuse[nb]);
 #pragma unroll
     for (int j = 0; j < kRowBlocks; ++j) fa[j] = *(const half8*)(frag + j * 256);
     if constexpr (kUnscatter) {
@@ -229,18 +220,18 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
           acc[j][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[j], fb[nb], acc[j][nb], 0, 0, 0);
     }
   } else {
-    // prologue: ring filled, first tile in LDS, first X chunk in LDS
-    xload(xr, 0);
+    // Rings: NS tiles of W words in flight; X fragments XS - 1 tiles ahead (they come from L2 and
+    // ride behind the words in the same in-order load queue).  Prologue: both rings filled, first
+    // tile in LDS.
+    u32x4 s[NS][R];
+    uint32_t sb[NS], se[NS];
+    u32x4 xq[XS][NB];
+#pragma unroll
+    for (int i = 0; i < XS - 1; ++i) xissue(xq[i]);
 #pragma unroll
     for (int i = 0; i < NS; ++i) issue(s[i], sb[i], se[i]);
     uint32_t next_window = window_at(t0 + NS);
     extract(s[0], sb[0], se[0]);
-    xstore(xr, 0);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-
-    constexpr int kChunksPerBody = NS / kWideWaves;
     for (uint32_t body = 0; body < bodies; ++body) {
       // refills of this body ask for tiles t0 + NS * body + NS ... + 2 NS - 1: inside the window
       // that starts at t0 + NS * (body + 1)
@@ -248,24 +239,13 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
       wbase = t0 + NS * (body + 1);
       next_window = window_at(t0 + NS * (body + 2));
 #pragma unroll
-      for (int c = 0; c < kChunksPerBody; ++c) {
-        const uint32_t chunk = body * kChunksPerBody + c;
-        xload(xr, chunk + 1);
-#pragma unroll
-        for (int j = 0; j < kWideWaves; ++j) {
-          const int i = c * kWideWaves + j, i1 = (i + 1) % NS;  // stages of this tile and of the next
-          step(s[i], sb[i], se[i], s[i1], sb[i1], se[i1], xbuf + (chunk & 1u) * kXChunkBytes + j * kXTileBytes);
-        }
-        xstore(xr, (chunk + 1) & 1u);
-        // the chunk just written is complete, and nobody still reads the one written next
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+      for (int i = 0; i < NS; ++i) {
+        const int i1 = (i + 1) % NS;  // stage of the next tile
+        step(s[i], sb[i], se[i], s[i1], sb[i1], se[i1], xq[(i + XS - 1) % XS], xq[i % XS]);
       }
     }
   }
 
-  if (!active) return;
   if (p.S == 1) {
     OutParams o;
     o.C = p.C;
@@ -312,16 +292,16 @@ __global__ __launch_bounds__(256) void wide_reduce_kernel(WideParams p) {
   }
 }
 
-template <int R, int NS>
+template <int R, int NS, int XS>
 static hipError_t launch_wide_variant(const WideParams& p, int grid, hipStream_t stream) {
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)spmm_wide_kernel<R, NS>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    hipError_t e = hipFuncSetAttribute((const void*)spmm_wide_kernel<R, NS, XS>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        kWideLdsBytes);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL((spmm_wide_kernel<R, NS>), dim3(grid), dim3(kWideWaves * 64), kWideLdsBytes, stream, p);
+  hipLaunchKernelGGL((spmm_wide_kernel<R, NS, XS>), dim3(grid), dim3(kWideWaves * 64), kWideLdsBytes, stream, p);
   return hipGetLastError();
 }
 
@@ -357,12 +337,12 @@ hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, hipStream_t stream
   p.S = wide_slices(p.bands, p.KT, a.num_cus);
   const int grid = (int)(groups * p.S);
   hipError_t e;
-  // rounds of 256 words staged per tile; the ring is 8 tiles deep while the registers allow
-  if (a.max_tile_words <= 2 * 256) e = launch_wide_variant<2, 8>(p, grid, stream);
-  else if (a.max_tile_words <= 3 * 256) e = launch_wide_variant<3, 8>(p, grid, stream);
-  else if (a.max_tile_words <= 4 * 256) e = launch_wide_variant<4, 8>(p, grid, stream);
-  else if (a.max_tile_words <= 6 * 256) e = launch_wide_variant<6, 4>(p, grid, stream);
-  else e = launch_wide_variant<8, 4>(p, grid, stream);
+  // rounds of 256 words staged per tile; the ring is 8 tiles deep while the registers allow; X fragments 3 tiles ahead
+  if (a.max_tile_words <= 2 * 256) e = launch_wide_variant<2, 8, 4>(p, grid, stream);
+  else if (a.max_tile_words <= 3 * 256) e = launch_wide_variant<3, 8, 4>(p, grid, stream);
+  else if (a.max_tile_words <= 4 * 256) e = launch_wide_variant<4, 8, 4>(p, grid, stream);
+  else if (a.max_tile_words <= 6 * 256) e = launch_wide_variant<6, 4, 4>(p, grid, stream);
+  else e = launch_wide_variant<8, 4, 4>(p, grid, stream);
   if (e != hipSuccess) return e;
   if (p.S > 1) e = launch_wide_reduce(p, stream);
   return e;
