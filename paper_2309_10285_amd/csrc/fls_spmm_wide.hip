@@ -24,6 +24,12 @@
 #include "fls_device.h"
 #include "fls_launch.h"
 
+// Latency-breakdown builds (see fls_spmm.hip): 2 no MFMA, 4 no extract, 8 no re-zeroing, 16 no LDS
+// fragment reads, 32 no global loads of the words, 256 no loads of X.  0 in the library.
+#ifndef FLS_ABLATE
+#define FLS_ABLATE 0
+#endif
+
 namespace fls {
 
 constexpr int kWideWaves = 4;                   // = bands per group
@@ -90,7 +96,8 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       const bool wanted = xti < k1 && (uint32_t)nb < xvalid;
-      xq[nb] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, wanted ? base + nb * 1024u : 0xffffff00u, 0, 0);  // else: 0
+      if (FLS_ABLATE & 256) xq[nb] = u32x4{base, 1u, 2u, 3u};
+      else xq[nb] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, wanted ? base + nb * 1024u : 0xffffff00u, 0, 0);  // else: 0
     }
     ++xti;
   };
@@ -117,7 +124,10 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
     const __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void*)(p.words + begin), 0, (int)(n * 4u), kBufferFlags);
 #pragma unroll
-    for (int r = 0; r < R; ++r) s[r] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (r * 64 + lane) * 16, 0, kAuxNonTemporal);
+    for (int r = 0; r < R; ++r) {
+      if (FLS_ABLATE & 32) s[r] = u32x4{(uint32_t)lane, 1u, 2u, 3u};
+      else s[r] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (r * 64 + lane) * 16, 0, kAuxNonTemporal);
+    }
     ++ti;
   };
 
@@ -136,7 +146,8 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
       for (int j = 0; j < 4; ++j) {
         const uint32_t w = s[r][j];
         const uint32_t addr = scatter_addr(w, base);
-        *(lds_u16_ptr)(uintptr_t)addr = (uint16_t)(w >> 16);
+        if (FLS_ABLATE & 4) asm volatile("" ::"v"(w));
+        else *(lds_u16_ptr)(uintptr_t)addr = (uint16_t)(w >> 16);
         s[r][j] = addr;
       }
     }
@@ -165,8 +176,12 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) fb[nb] = __builtin_bit_cast(half8, xuse[nb]);
 #pragma unroll
-    for (int j = 0; j < kRowBlocks; ++j) fa[j] = *(const half8*)(frag + j * 256);
-    if constexpr (kUnscatter) {
+    for (int j = 0; j < kRowBlocks; ++j) {
+      if (FLS_ABLATE & 16) fa[j] = fb[j % NB];
+      else fa[j] = *(const half8*)(frag + j * 256);
+    }
+    if (FLS_ABLATE & 8) {
+    } else if constexpr (kUnscatter) {
       unscatter(cur);
     } else {
 #pragma unroll
@@ -177,8 +192,10 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
 #pragma unroll
     for (int j = 0; j < kRowBlocks; ++j)
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-        acc[j][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[j], fb[nb], acc[j][nb], 0, 0, 0);
+      for (int nb = 0; nb < NB; ++nb) {
+        if (FLS_ABLATE & 2) acc[j][nb][0] += (float)fa[j][0] * (float)fb[nb][0];
+        else acc[j][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[j], fb[nb], acc[j][nb], 0, 0, 0);
+      }
     // asks the scheduler for: one MFMA, then up to three instructions of the other kinds
 #pragma unroll
     for (int i = 0; i < kRowBlocks * NB; ++i) {

@@ -1,7 +1,8 @@
 """Latency breakdown of fls_spmm by erasing operations (the method of the paper's Fig. 11, Sec. 6.2.1).
 
 Builds copies of libfls.so with -DFLS_ABLATE=<mask> (see csrc/fls_spmm.hip: 1 no split-K hand-over,
-2 no MFMA, 4 no extract, 8 no re-zeroing, 16 no LDS fragment reads, 32 no global loads of the words),
+2 no MFMA, 4 no extract, 8 no re-zeroing, 16 no LDS fragment reads, 32 no global loads of the words,
+256 no loads of X in the 64-column pass, which has no hand-over and ignores bit 1),
 times each on one benchmark configuration and prints one JSON line per build.  Results of the ablated
 builds are wrong by design; only their times mean something.  The builds go to a scratch folder
 (default: a temporary directory), never into the package.
@@ -36,6 +37,8 @@ VARIANTS = [
     ("global loads only (W and X)", 1 | 2 | 4 | 8 | 16),
     ("LDS + MFMA work only (no W loads)", 1 | 32),
     ("loop skeleton and X loads only", 1 | 2 | 4 | 8 | 16 | 32),
+    ("no hand-over, no X loads (64-column pass)", 1 | 256),
+    ("loop skeleton only (64-column pass)", 1 | 2 | 4 | 8 | 16 | 32 | 256),
 ]
 
 
