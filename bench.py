@@ -33,6 +33,10 @@ def _time_loop(calls, steps, warmup):
     import torch
 
     n = len(calls)
+    # one call per copy first: fls_spmm reads a blob's header back (and waits) the first time it sees its address
+    for c in calls:
+        c()
+    torch.cuda.synchronize()
     # the GPU's clocks settle only after some tens of milliseconds of work: run untimed launches for that long
     # first, whatever the warm-up count asked for is
     t_end = time.perf_counter() + 0.03

@@ -38,19 +38,27 @@ constexpr int kWideTileLds = kTileBytes + 16;   // a wave's tile + the slot padd
 constexpr int kWideLdsBytes = kWideWaves * kWideTileLds;
 
 // X in MFMA fragment order: block (K tile kt, column block nb) holds, for lane l = 16 g + c, the 8
-// halves X[32 kt + 8 g .. +7][16 nb + c] (zeros for columns past N).  One wave per block; loads are
+// halves X[32 kt + 8 g .. +7][16 nb + c] (zeros for columns past N).  One wave per pair of K tiles
+// and column block, so that it uses the whole 128 B line of each of its 16 columns; loads are
 // quad-contiguous (lane j reads column j >> 2, chunk j & 3), stores go to the fragment position.
 __global__ __launch_bounds__(256) void xpack_kernel(const _Float16* X, _Float16* Xp, uint32_t K, uint32_t N, uint32_t units,
                                                     uint32_t blocks) {
-  const uint32_t u = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const uint32_t u = blockIdx.x * 4 + (threadIdx.x >> 6);  // (pair of K tiles, column block)
   if (u >= units) return;
   const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t kt = u / blocks, nb = u - kt * blocks;
+  const uint32_t pair = u / blocks, nb = u - pair * blocks;
   const uint32_t c = lane >> 2, g = lane & 3u;
   const uint32_t col = nb * 16u + c;
-  u32x4 v = {0u, 0u, 0u, 0u};
-  if (col < N) v = *(const u32x4*)(X + (size_t)col * K + kt * kTileK + g * 8u);
-  *(u32x4*)(Xp + ((size_t)u * 64u + g * 16u + c) * 8u) = v;
+  const uint32_t KT = K / kTileK;
+#pragma unroll
+  for (uint32_t h = 0; h < 2; ++h) {
+    const uint32_t kt = 2u * pair + h;
+    if (kt < KT) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (col < N) v = *(const u32x4*)(X + (size_t)col * K + kt * kTileK + g * 8u);
+      *(u32x4*)(Xp + (((size_t)kt * blocks + nb) * 64u + g * 16u + c) * 8u) = v;
+    }
+  }
 }
 
 template <int R, int NS, int XS>
@@ -324,7 +332,7 @@ static hipError_t launch_wide_variant(const WideParams& p, int grid, hipStream_t
 
 // X (all N columns of the call) into fragment order, once per call.
 hipError_t launch_xpack(const _Float16* X, _Float16* xpack, uint32_t K, uint32_t N, hipStream_t stream) {
-  const uint32_t blocks = (N + 15u) / 16u, units = (K / kTileK) * blocks;
+  const uint32_t blocks = (N + 15u) / 16u, units = ((K / kTileK + 1u) / 2u) * blocks;
   hipLaunchKernelGGL(xpack_kernel, dim3((units + 3) / 4), dim3(256), 0, stream, X, xpack, K, N, units, blocks);
   return hipGetLastError();
 }
