@@ -90,8 +90,11 @@ def run_sweep(args):
     for N in wl.SWEEP_NS:
         D = torch.empty((N, M), dtype=torch.float16, device="cuda")
         dense_ms[N], _ = _time_loop([fls.prepare_dense_gemm(w, Xd[N], D, M, K, N) for w in dense], args.steps, args.warmup)
+        V = torch.empty((N, M), dtype=torch.float16, device="cuda")
+        vms, _ = _time_loop([lambda w=w, x=Xd[N], v=V: torch.matmul(x, w.t(), out=v) for w in dense], args.steps, args.warmup)
         emit({"point": f"dense-N{N}", "N": N, "us": round(dense_ms[N] * 1e3, 2),
-              "GBps": round((2 * M * K + 2 * K * N + 2 * M * N) / dense_ms[N] / 1e6, 1)})
+              "GBps": round((2 * M * K + 2 * K * N + 2 * M * N) / dense_ms[N] / 1e6, 1),
+              "vendor_gemm_us": round(vms * 1e3, 2)})
     del dense, Wd
     worst = 0.0
     for mask in wl.SWEEP_MASKS:
@@ -300,6 +303,12 @@ def main():
                              "achieved_GBps": round(dbytes / (dms * 1e-3) / 1e9, 1),
                              "hbm_frac": round(dbytes / (dms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                              "spmm_speedup": round(dms / ms, 3), "copies_rotated": n_d}
+        # context only: the vendor library's GEMM on the same operands and layouts (the paper's dense baseline is
+        # the vendor library, Sec. 6.1), through torch.matmul (rocBLAS / hipBLASLt); C[N, M] = X[N, K] . W[M, K]^T
+        V = torch.empty((N, M), dtype=torch.float16, device="cuda")
+        vms, _ = _time_loop([lambda w=w: torch.matmul(X, w.t(), out=V) for w in dense], args.steps, args.warmup)
+        out["vendor_gemm"] = {"library": "torch.matmul (rocBLAS / hipBLASLt)", "ms_per_step": round(vms, 5),
+                              "achieved_GBps": round(dbytes / (vms * 1e-3) / 1e9, 1), "spmm_speedup": round(vms / ms, 3)}
         del dense, Wd
 
     if not args.no_cpu_baseline:
