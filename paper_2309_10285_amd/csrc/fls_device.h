@@ -100,10 +100,11 @@ __device__ __forceinline__ void store_band(const OutParams& o, const float4v (&a
 template <int NB>
 struct WgReduceLds {
   static constexpr uint32_t kSlots = 2;
+  static constexpr int kParts = 4;  // a slot is added to in four parts, each under its own lock
   float4v slot[kSlots][NB * kRowBlocks * 64];
-  uint32_t cnt[2];   // tiles added to the slot so far
-  uint32_t gen[2];   // how many bands the slot has served
-  uint32_t lock[2];  // 1 while a wave is adding to the slot
+  uint32_t cnt[2];           // tiles added to the slot so far
+  uint32_t gen[2];           // how many bands the slot has served
+  uint32_t lock[2][kParts];  // 1 while a wave is adding to that part of the slot
 };
 
 template <int NB>
@@ -112,16 +113,19 @@ __device__ __forceinline__ void wg_reduce_init(WgReduceLds<NB>* red, int tid, in
   if (tid < 2) {
     red->cnt[tid] = 0;
     red->gen[tid] = 0;
-    red->lock[tid] = 0;
+#pragma unroll
+    for (int part = 0; part < WgReduceLds<NB>::kParts; ++part) red->lock[tid][part] = 0;
   }
 }
 
 // Adds a wave's accumulators for the seq-th band of its workgroup (seq counts from the
 // workgroup's first band) to the band's slot.  Returns true for exactly one wave per band: the
 // one whose tiles complete `expected`; the slot then holds the workgroup's sum (wg_reduce_take
-// collects it).  Waves take turns on a slot under a spin lock and add with plain 16 B
-// read-add-write; LDS floating-point atomics would need no lock but run about fifty times
-// slower per instruction on this chip than a plain LDS access.
+// collects it).  Waves add with plain 16 B read-add-write under spin locks, one per quarter of
+// the slot, all taking the quarters in the same order: waves that arrive together follow each
+// other through the slot like an assembly line instead of waiting for the whole of it.  (LDS
+// floating-point atomics would need no lock but run about fifty times slower per instruction
+// on this chip than a plain LDS access.)
 template <int NB>
 __device__ __forceinline__ bool wg_reduce_add(WgReduceLds<NB>* red, const float4v (&acc)[kRowBlocks][NB], uint32_t seq,
                                               uint32_t tiles, uint32_t expected, int lane) {
@@ -129,25 +133,25 @@ __device__ __forceinline__ bool wg_reduce_add(WgReduceLds<NB>* red, const float4
   // the slot may still serve an earlier band (only when a share spans more bands than there are slots)
   while (__hip_atomic_load(&red->gen[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) != turn)
     __builtin_amdgcn_s_sleep(2);
-  for (;;) {
-    uint32_t got = 1;
-    if (lane == 0) got = __hip_atomic_exchange(&red->lock[s], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    if (__builtin_amdgcn_readfirstlane(got) == 0) break;
-    __builtin_amdgcn_s_sleep(1);
-  }
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  constexpr int kParts = WgReduceLds<NB>::kParts, kPerPart = NB * kRowBlocks / kParts;
   float4v* d = &red->slot[s][lane];
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb)
+  for (int part = 0; part < kParts; ++part) {
+    for (;;) {
+      uint32_t got = 1;
+      if (lane == 0) got = __hip_atomic_exchange(&red->lock[s][part], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      if (__builtin_amdgcn_readfirstlane(got) == 0) break;
+      __builtin_amdgcn_s_sleep(1);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 #pragma unroll
-    for (int rb = 0; rb < kRowBlocks; ++rb) d[(nb * kRowBlocks + rb) * 64] += acc[rb][nb];
-  uint32_t old = 0;
-  if (lane == 0) {
-    old = red->cnt[s];
-    red->cnt[s] = old + tiles;
+    for (int e = part * kPerPart; e < (part + 1) * kPerPart; ++e) d[e * 64] += acc[e % kRowBlocks][e / kRowBlocks];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    if (lane == 0) __hip_atomic_store(&red->lock[s][part], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
   }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-  if (lane == 0) __hip_atomic_store(&red->lock[s], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  // counted in after the last part: the wave that completes the count finds every part added
+  uint32_t old = 0;
+  if (lane == 0) old = __hip_atomic_fetch_add(&red->cnt[s], tiles, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
   old = __builtin_amdgcn_readfirstlane(old);
   return old + tiles == expected;
 }
