@@ -122,16 +122,16 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     const uint32_t n = end - begin;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      const uint32_t q = r * 64 + lane;
-      if (q * 4 < n) {
+      // no branch: a lane past the end of the run (its loads returned 0: location 0, value 0) gets
+      // the slot that padding words go to as its base
+      const uint32_t base = (r * 64 + lane) * 4u < n ? tile_addr : tile_addr + (uint32_t)kTileBytes;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const uint32_t w = s[r][j];
-          const uint32_t addr = scatter_addr(w, tile_addr);
-          if (FLS_ABLATE & 4) asm volatile("" ::"v"(w));
-          else *(lds_u16_ptr)(uintptr_t)addr = (uint16_t)(w >> 16);
-          s[r][j] = addr;
-        }
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t w = s[r][j];
+        const uint32_t addr = scatter_addr(w, base);
+        if (FLS_ABLATE & 4) asm volatile("" ::"v"(w));
+        else *(lds_u16_ptr)(uintptr_t)addr = (uint16_t)(w >> 16);
+        s[r][j] = addr;
       }
     }
     if (n > R * 256u) extract_overflow(p.words, begin + R * 256u, end, tile);
@@ -148,13 +148,9 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
       for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
     } else {
 #pragma unroll
-      for (int r = 0; r < R; ++r) {
-        const uint32_t q = r * 64 + lane;
-        if (q * 4 < n) {
+      for (int r = 0; r < R; ++r)
 #pragma unroll
-          for (int j = 0; j < 4; ++j) *(lds_u16_ptr)(uintptr_t)s[r][j] = (uint16_t)0;
-        }
-      }
+        for (int j = 0; j < 4; ++j) *(lds_u16_ptr)(uintptr_t)s[r][j] = (uint16_t)0;
     }
   };
   auto read_frags = [&](half8(&a)[kRowBlocks]) {
