@@ -55,6 +55,16 @@ inline uint32_t wide_slices(uint32_t bands, uint32_t KT, int cus) {
   const uint32_t by_length = KT / 16u > 0 ? KT / 16u : 1u;
   return S < by_length ? S : by_length;
 }
+// The sparse 64-column pass: a workgroup takes two bands and a K slice, two waves per band (one
+// per half of the slice), and writes one partial result per band and slice.  Slices per pair of
+// bands: as many as fill the CUs, none shorter than 32 tiles (16 per wave).
+inline uint32_t wide_pair_slices(uint32_t bands, uint32_t KT, int cus) {
+  if (cus > (int)kMaxWorkgroups) cus = (int)kMaxWorkgroups;
+  const uint32_t pairs = (bands + 1) / 2;
+  uint32_t S = pairs < (uint32_t)cus ? (uint32_t)cus / pairs : 1u;
+  const uint32_t by_length = KT / 32u > 0 ? KT / 32u : 1u;
+  return S < by_length ? S : by_length;
+}
 // fp32 values of the split-K partial sums: [workgroup][column blocks][128 x 16] for the passes of
 // up to 32 columns, [band][slice][4][128 x 16] for the 64-column pass
 inline size_t parts_floats(uint32_t N) {

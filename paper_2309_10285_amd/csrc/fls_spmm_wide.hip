@@ -2,8 +2,8 @@
 // sizes, re-cut for gfx950).
 //
 // A workgroup has four waves, one per SIMD with the whole register file (128 accumulator
-// registers, a deep ring of tiles in flight), each on its own row band; the waves share nothing
-// but the CU: no barrier, no waiting.  With 64 columns a tile needs 4 KB of X against some
+// registers, a deep ring of tiles in flight), each with a tile run of its own; in the tile loop
+// the waves share nothing but the CU: no barrier, no waiting.  With 64 columns a tile needs 4 KB of X against some
 // 1.6 - 5 KB of compressed W, so how X reaches the MFMAs matters as much as W: a first kernel
 // repacks X once per call into MFMA fragment order, after which a wave's four B fragments of a K
 // tile are four fully coalesced 1 KB loads from L2, kept a few tiles ahead in a register ring of
@@ -12,10 +12,13 @@
 // chunks, one barrier per four tiles - costs LDS bandwidth and lockstep, and measured 6 - 10 %
 // slower for sparse tiles.)
 //
-// Work is cut as (group of four bands) x (K slice): S slices per group so that the grid fills
-// the CUs.  A wave's accumulators are its band's partial result for its slice: with S = 1 they are
-// stored to C directly, otherwise to a partial-sum area [band][slice] that a second, small kernel
-// adds up in slice order and converts (no flags, no waiting between workgroups).
+// Work is cut as (pair of bands) x (K slice), S slices per pair so that the grid fills the CUs;
+// inside a workgroup each band has two waves, one per half of the slice, whose accumulators meet
+// in LDS when both are done (the one barrier of the kernel).  The sum is the band's partial
+// result for the slice: with S = 1 it is stored to C directly, otherwise to a partial-sum area
+// [band][slice] that a second, small kernel adds up in slice order and converts (no flags, no
+// waiting between workgroups).  Two waves per band halve the partial sums that go through memory
+// against one wave per band and slice.
 //
 // Inside a wave the stages are those of the narrow kernel - register ring of tiles, extraction by
 // 2 B LDS stores, 16 B fragment reads, v_mfma_f32_16x16x32_f16 - software-pipelined, since no
@@ -32,10 +35,10 @@
 
 namespace fls {
 
-constexpr int kWideWaves = 4;                   // = bands per group
+constexpr int kWideWaves = 4;                   // two bands x two halves of the K slice
 constexpr int kWideNB = 4;                      // column blocks per pass
 constexpr int kWideTileLds = kTileBytes + 16;   // a wave's tile + the slot padding words land in
-constexpr int kWideLdsBytes = kWideWaves * kWideTileLds;
+constexpr int kWideLdsBytes = kWideWaves * kWideTileLds + 2 * kWideNB * kRowBlocks * 64 * 16;  // tiles + two bands' accumulators
 
 // X in MFMA fragment order: block (K tile kt, column block nb) holds, for lane l = 16 g + c, the 8
 // halves X[32 kt + 8 g .. +7][16 nb + c] (zeros for columns past N).  One wave per pair of K tiles
@@ -68,12 +71,15 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   extern __shared__ __align__(16) unsigned char lds[];
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const uint32_t group = blockIdx.x / p.S, slice = blockIdx.x - group * p.S;
-  const uint32_t band = group * kWideWaves + wave;
-  if (band >= p.bands) return;  // the waves of a workgroup share nothing but the CU
+  // the workgroup: two row bands x the two halves of its K slice
+  const uint32_t pair = blockIdx.x / p.S, slice = blockIdx.x - pair * p.S;
+  const uint32_t band = pair * 2 + (wave & 1u), half = wave >> 1;
+  const bool active = band < p.bands;  // a wave past the last band walks an empty run and meets the barrier
   const uint32_t KT = p.KT, T = p.bands * KT;
-  const uint32_t k0 = (uint32_t)((uint64_t)slice * KT / p.S), k1 = (uint32_t)((uint64_t)(slice + 1) * KT / p.S);
-  const uint32_t t0 = band * KT + k0, t1 = band * KT + k1;
+  const uint32_t ka = (uint32_t)((uint64_t)slice * KT / p.S), kb = (uint32_t)((uint64_t)(slice + 1) * KT / p.S);
+  const uint32_t km = ka + (kb - ka + 1) / 2;
+  const uint32_t k0 = half ? km : ka, k1 = active ? (half ? kb : km) : k0;
+  const uint32_t t0 = active ? band * KT + k0 : T, t1 = active ? band * KT + k1 : T;
   const uint32_t bodies = (k1 - k0 + NS - 1) / NS;  // of NS steps each
 
   unsigned char* tile = lds + wave * kWideTileLds;
@@ -271,6 +277,22 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
     }
   }
 
+  // The two halves of the K slice meet in LDS: the waves of the second half leave their
+  // accumulators there, the waves of the first half add them to their own and write the band's
+  // result for the slice - half as many partial sums in memory as waves.
+  float4v* meet = (float4v*)(lds + kWideWaves * kWideTileLds) + (wave & 1u) * (NB * kRowBlocks * 64) + lane;
+  if (half == 1) {
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int rb = 0; rb < kRowBlocks; ++rb) meet[(nb * kRowBlocks + rb) * 64] = acc[rb][nb];
+  }
+  __syncthreads();
+  if (half == 1 || !active) return;
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int rb = 0; rb < kRowBlocks; ++rb) acc[rb][nb] += meet[(nb * kRowBlocks + rb) * 64];
   if (p.S == 1) {
     OutParams o;
     o.C = p.C;
@@ -358,9 +380,9 @@ hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, hipStream_t stream
   p.n0 = n0;
   p.KT = a.K / kTileK;
   p.bands = a.M / kTileM;
-  const uint32_t groups = (p.bands + kWideWaves - 1) / kWideWaves;
-  p.S = wide_slices(p.bands, p.KT, a.num_cus);
-  const int grid = (int)(groups * p.S);
+  const uint32_t pairs = (p.bands + 1u) / 2u;
+  p.S = wide_pair_slices(p.bands, p.KT, a.num_cus);
+  const int grid = (int)(pairs * p.S);
   hipError_t e;
   // rounds of 256 words staged per tile; the ring is 8 tiles deep while the registers allow; X fragments 3 tiles ahead
   if (a.max_tile_words <= 2 * 256) e = launch_wide_variant<2, 8, 4>(p, grid, stream);
