@@ -16,7 +16,8 @@
  *   - M must be a multiple of FLS_TILE_M, K of FLS_TILE_K; 1 <= N <= FLS_MAX_N
  *   - device pointers must be 16-byte aligned
  *   - kernels are enqueued on `stream` and the call returns without waiting, except
- *     fls_compress, which waits for its own work (it is an offline step, Sec. 5)
+ *     fls_compress, which waits for its own work (it is an offline step, Sec. 5), the first
+ *     fls_spmm on a blob address (header read-back) and fls_check_workspace
  *   - every function returns FLS_OK (0) or a negative error code; arguments are checked on
  *     the host before anything is launched, so a failed call has launched nothing
  *   - one device per process is assumed: calls act on the current HIP device
