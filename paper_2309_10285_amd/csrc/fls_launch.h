@@ -83,7 +83,8 @@ inline size_t xpack_bytes(uint32_t K, uint32_t N) {
 // k = 1 no partial sum ever crosses between workgroups, and the serial hand-over chain at the end
 // of the kernel (store, count, read back: a few microseconds with the whole chip waiting) goes
 // away.  That is worth leaving up to a fifth of the CUs without a workgroup: the kernel is paced by
-// HBM, not by the CUs.  Otherwise every CU gets an equal share, cut wherever it falls.
+// HBM, not by the CUs.  Otherwise every CU gets an equal share, cut wherever it falls (see below
+// for the one exception).
 // A workgroup should also have enough tiles to amortise its start and its hand-over: small
 // problems get fewer workgroups (at least kMinShare tiles each).
 constexpr uint32_t kMinShare = 32;
@@ -94,6 +95,12 @@ inline int pick_grid(uint32_t bands, uint32_t tiles_per_band, int cus) {
   if ((int)bands <= cus) {
     const int aligned = (int)bands * (cus / (int)bands);
     if (aligned * 5 >= cus * 4) return aligned;
+    // next best: every pair of bands to an odd number of workgroups (only the middle one of each
+    // group spans two bands), if that leaves next to no CU idle - 168 bands on 256 CUs: 252
+    // workgroups measured 3 % faster than 256
+    const int j = 2 * cus / (int)bands;
+    const int halves = (int)bands * j;
+    if (halves % 2 == 0 && halves / 2 * 100 >= cus * 97) return halves / 2;
   }
   return cus;
 }
