@@ -44,10 +44,10 @@ constexpr uint32_t kGroupCols = 32;
 constexpr uint32_t kSpmmGroupCols = 64;
 inline uint32_t group_blocks(uint32_t ncols) { return ncols <= 16 ? 1u : (ncols <= 32 ? 2u : 4u); }
 constexpr uint32_t kMaxWorkgroups = 512;    // must equal fls::kMaxGrid of the device code
-// The 64-column pass of the sparse kernel cuts its work as (group of 4 bands) x (K slice) and
-// keeps one 128 x 64 fp32 partial result per band and slice.  Slices per group: as many as fill
-// the CUs, but none shorter than 16 tiles.  groups * slices <= kMaxWorkgroups, so bands * slices
-// <= 4 * kMaxWorkgroups partial results at most.
+// The 64-column pass of the dense kernel cuts its work as (group of 4 bands) x (K slice), one wave
+// per band, and keeps one 128 x 64 fp32 partial result per band and slice.  Slices per group: as
+// many as fill the CUs, but none shorter than 16 steps.  groups * slices <= kMaxWorkgroups, so
+// bands * slices <= 4 * kMaxWorkgroups partial results at most (what parts_floats provides).
 inline uint32_t wide_slices(uint32_t bands, uint32_t KT, int cus) {
   if (cus > (int)kMaxWorkgroups) cus = (int)kMaxWorkgroups;
   const uint32_t groups = (bands + 3) / 4;
