@@ -30,9 +30,11 @@ struct OffsetWindow {
     request(t);
     arrive();
   }
-  // offsets of tiles t and t + 1 (reloads the window when t + 1 falls outside it)
+  // offsets of tiles t and t + 1; reloads the window when t or t + 1 falls outside it - t may lie
+  // before the window: the load side looks a few tiles past the end of a piece, which can move the
+  // window beyond the tile the next piece starts with
   __device__ __forceinline__ void get(uint32_t t, uint32_t& begin, uint32_t& end) {
-    if (t + 1 - base > 63u) load(t);
+    if (t - base > 62u) load(t);
     begin = (uint32_t)__builtin_amdgcn_readlane((int)window, (int)(t - base));
     end = (uint32_t)__builtin_amdgcn_readlane((int)window, (int)(t + 1 - base));
   }

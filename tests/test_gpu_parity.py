@@ -429,3 +429,30 @@ def test_check_workspace_reports_a_hand_over_that_gave_up(fls, oracle_mod):
     _, _, C = _run_spmm(fls, W, X, 16)
     assert _rel_err(C, oracle_mod.ref_spmm_f64(W, X)) <= TOL
     fls.fls_check_workspace()
+
+
+def test_piece_boundary_at_the_edge_of_the_offset_window(fls, oracle_mod):
+    """Waves with more than 64 tiles whose run crosses into the next row band exactly at the last entry of their
+    window of TileOffsets: the load side looks past the end of the piece and moves the window on, and the next
+    piece starts one tile before the new window.  With 256 CUs that takes at least 129 000 tiles; this shape
+    (258 bands x 500 K tiles) has four such waves, in bands 65, 81, 194 and 210 (a first version read the wrong
+    offset there).  C is checked on those bands and their neighbours against the oracle."""
+    import torch
+
+    M, K, N = 258 * 128, 500 * 32, 16
+    W = wl.prune_uniform(wl.gen_weights_f32(M, K, 81), 0.9, 82)
+    X = wl.gen_x(N, K, 83)
+    blob, st = fls.fls_compress(_dev_w(W))
+    assert st["nnz"] == int(np.count_nonzero(W))
+    Xd = torch.from_numpy(X.view(np.float16)).cuda()
+    C = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+    fls.ensure_workspace(M, K, N)
+    fls.fls_spmm(blob, Xd, C, M, K, N)
+    torch.cuda.synchronize()
+    C = C.cpu().numpy()
+    assert not np.isnan(C).any()
+    for band in (0, 64, 65, 66, 81, 194, 210, 257):
+        m0, m1 = band * 128, band * 128 + 128
+        ref = oracle_mod.ref_spmm_f64(W[m0:m1], X)
+        assert _rel_err(C[:, m0:m1], ref) <= TOL, band
+    fls.fls_forget(blob)
