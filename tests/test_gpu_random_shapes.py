@@ -1,0 +1,74 @@
+"""Randomly drawn shapes, widths, sparsities and masks (seeded): fls_spmm and fls_dense_gemm through the C ABI
+against the oracle on sampled row bands.  The fixed cases of test_gpu_parity.py were chosen by thought; these
+are not, which is the point: a wrong answer for a shape nobody thought of shows up here."""
+import numpy as np
+import pytest
+
+import fls_workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3
+
+
+def _draw(seed, count):
+    g = np.random.Generator(np.random.Philox(seed))
+    out = []
+    for i in range(count):
+        M = 128 * int(g.integers(1, 65))
+        K = 32 * int(g.integers(1, 257))
+        N = int(g.integers(1, 257))
+        beta = float(g.choice([0.0, 0.3, 0.5, 0.6, 0.7, 0.8, 0.9, 0.95, 0.99, 1.0]))
+        mask = str(g.choice(["uniform", "uniform", "magnitude", "row_skewed"]))
+        out.append((i, M, K, N, beta, mask))
+    return out
+
+
+CASES = _draw(20240917, 30)
+
+
+@pytest.mark.parametrize("i,M,K,N,beta,mask", CASES, ids=[f"{c[1]}x{c[2]}-N{c[3]}-{int(c[4] * 100)}-{c[5]}" for c in CASES])
+def test_random_shape_matches_oracle(oracle_mod, i, M, K, N, beta, mask):
+    import torch
+
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2309_10285_amd as fls
+
+    fls.lib()
+    W32 = wl.gen_weights_f32(M, K, 1000 + i)
+    if beta >= 1.0:
+        W = np.zeros((M, K), dtype=np.uint16)
+    elif beta <= 0.0:
+        W = wl.dense_bits(W32)
+    elif mask == "magnitude":
+        W = wl.prune_magnitude(W32, beta)
+    elif mask == "row_skewed":
+        W = wl.prune_row_skewed(W32, beta, 2000 + i)
+    else:
+        W = wl.prune_uniform(W32, beta, 2000 + i)
+    X = wl.gen_x(N, K, 3000 + i)
+    Wd = torch.from_numpy(W.view(np.float16)).cuda()
+    Xd = torch.from_numpy(X.view(np.float16)).cuda()
+    blob, st = fls.fls_compress(Wd)
+    assert st["nnz"] == int(np.count_nonzero(W))
+    fls.ensure_workspace(M, K, N)
+    C = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+    D = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+    fls.fls_spmm(blob, Xd, C, M, K, N)
+    fls.fls_dense_gemm(Wd, Xd, D, M, K, N)
+    torch.cuda.synchronize()
+    C, D = C.cpu().numpy(), D.cpu().numpy()
+    assert not np.isnan(C).any() and not np.isnan(D).any()
+    bands = M // 128
+    scale = None
+    for band in sorted({0, bands // 2, bands - 1}):
+        m0, m1 = band * 128, band * 128 + 128
+        ref = oracle_mod.ref_spmm_f64(W[m0:m1], X)
+        scale = max(float(np.abs(ref).max()), 1e-30)
+        for got in (C, D):
+            assert float(np.abs(got[:, m0:m1].astype(np.float64) - ref).max()) / scale <= TOL, band
+    if beta >= 1.0:
+        assert not C.any() and not D.any()
+    fls.fls_forget(blob)
+    fls.fls_check_workspace()
