@@ -133,8 +133,10 @@ int fls_check_workspace(fls_stream_t stream);
 /*
  * C = W . X with W given as a Tiled-CSL blob (the SpMM of Alg. 1): streams the blob from HBM
  * (once per 64 columns for N > 32, else once), rebuilds each tile densely in LDS, multiplies
- * with MFMA, fp32 accumulation.  The result does not depend on timing: partial sums are added
- * in a fixed order.  2*K*N and 2*M*N must stay below 2^31 (32-bit byte offsets into X and C).
+ * with MFMA, fp32 accumulation.  Partial sums of different workgroups are added in a fixed order;
+ * inside a workgroup the waves' sums are added in the order they finish unless the workgroup's
+ * tiles lie in one row band (then in wave order), so two runs may differ in the last bit of an
+ * fp32 sum, never by more.  2*K*N and 2*M*N must stay below 2^31 (32-bit byte offsets into X and C).
  *   Wc_dev in : blob made by fls_compress (or byte-identical); its header must match M, K
  *   X_dev  in : fp16 column-major K x N;  C_dev out: fp16 column-major M x N (fully overwritten)
  * The first call on a given blob address reads its 64-byte header back (a copy on `stream`, waited for) to

@@ -190,14 +190,16 @@ __device__ __forceinline__ void wg_reduce_skip(WgReduceLds<NB>* red, uint32_t se
 // A band that is cut between workgroups is finished by its owner: the workgroup whose share holds
 // the band's first tile.  The owner's piece of the band is the last thing in its share, so its
 // sum is still in registers when its run ends.  Every other workgroup that holds tiles of the
-// band stores its sum to its slot when its piece ends (plain write-through stores, nothing waits
-// for them) and publishes the slot when its own run ends, by raising its flag after the stores
-// were acknowledged.  The owner then polls those flags, adds the slots in workgroup order (so the
-// result does not depend on timing) and writes fp16 C.
+// band stores its sum to its slot when its piece ends (write-through stores, nothing waits for
+// them) and publishes the slot when its own run ends, by raising its flag behind a device-scope
+// release.  The owner then polls those flags, acquires, adds the slots in workgroup order and
+// writes fp16 C.
 //
-// Partial sums cross between the L2 caches of different XCDs: they are written through to memory
-// and read past the caches access by access (sc1 on the instruction), so no cache-wide write-back
-// or invalidate - what a device-scope fence costs - is needed.  A workgroup publishes at most one
+// Partial sums cross between the L2 caches of different XCDs, which are not coherent with each
+// other inside a kernel: the contributor releases at device scope before it raises its flag, the
+// owner acquires at device scope after it has seen the flags (2 - 3 us of the kernel's tail on
+// shapes that split bands; the stores and loads of the slots also carry sc1, so little is left for
+// the release to write back).  A workgroup publishes at most one
 // partial sum per launch (only the first band of a share can begin outside it) and exactly one
 // owner waits for it; the owner lowers the flag it has seen, so all flags are down again when the
 // launch ends: nothing is cleared between calls, and a launch recorded in a graph can be replayed.
@@ -221,7 +223,11 @@ __device__ __forceinline__ void store_partial(const OutParams& o, const float4v 
 
 // By the wave that called store_partial, once its run is over.
 __device__ __forceinline__ void publish_partial(const OutParams& o, uint32_t wg, int lane) {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // s_waitcnt vmcnt(0): the stores are acknowledged
+  // A device-scope release: the L2 of this XCD writes back what it holds and the wave waits for
+  // that.  Waiting for the stores alone (s_waitcnt vmcnt(0)) is not enough: a store counts as done
+  // when the XCD's L2 has it, and the flag could reach memory before the data does (seen as a wrong
+  // band about once in a thousand calls).
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
   if (lane == 0) __hip_atomic_store(o.flags + wg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
@@ -246,6 +252,9 @@ __device__ __forceinline__ void owner_finish(const OutParams& o, float4v (&acc)[
     if (seen && lane == 0) __hip_atomic_store(o.flags + q, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   FLS_STAMP(o.flags, wg, 6);
+  // the acquire that pairs with the contributors' release: nothing this XCD's caches still hold of
+  // the slots may serve the loads below
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
   // As many loads as the registers allow are issued before the first is used: each is a trip
   // to memory, and this runs when the kernel is about to end, with nothing left to hide it behind.
   constexpr int kBatch = NB == 1 ? 4 : 2;  // slots in flight

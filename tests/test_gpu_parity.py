@@ -456,3 +456,38 @@ def test_piece_boundary_at_the_edge_of_the_offset_window(fls, oracle_mod):
         ref = oracle_mod.ref_spmm_f64(W[m0:m1], X)
         assert _rel_err(C[:, m0:m1], ref) <= TOL, band
     fls.fls_forget(blob)
+
+
+def test_split_bands_after_wide_passes_many_repeats(fls, oracle_mod):
+    """N = 222 on a matrix whose bands are cut between workgroups: three 64-column passes, then a 32-column pass
+    whose partial-sum slots lie where the wide passes' partial results were a moment ago.  A hand-over that raised
+    its flag before its partial sum had left the XCD's L2 gave a wrong band about once in a thousand such calls;
+    the first result is checked against the oracle on sampled bands, then 3000 more calls must repeat it to within
+    fp16 rounding (inside a workgroup the waves' sums are added in the order they finish, so the last bit may
+    differ; a wrong band is off by tens of percent)."""
+    import torch
+
+    M, K, N = 24960, 9216, 222
+    W = wl.prune_uniform(wl.gen_weights_f32(M, K, 91), 0.9, 92)
+    X = wl.gen_x(N, K, 93)
+    blob, st = fls.fls_compress(_dev_w(W))
+    Xd = torch.from_numpy(X.view(np.float16)).cuda()
+    fls.ensure_workspace(M, K, N)
+    first = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+    fls.fls_spmm(blob, Xd, first, M, K, N)
+    torch.cuda.synchronize()
+    got = first.cpu().numpy()
+    for band in (0, 77, M // 128 - 1):
+        m0, m1 = band * 128, band * 128 + 128
+        assert _rel_err(got[:, m0:m1], oracle_mod.ref_spmm_f64(W[m0:m1], X)) <= TOL
+    C = torch.empty_like(first)
+    ref32 = first.float()
+    scale = float(ref32.abs().max())
+    worst = torch.zeros((), device="cuda")
+    for rep in range(3000):
+        C.fill_(float("nan"))
+        fls.fls_spmm(blob, Xd, C, M, K, N)
+        worst = torch.maximum(worst, torch.nan_to_num((C.float() - ref32).abs(), nan=float("inf")).max())
+    assert float(worst) / scale <= TOL
+    fls.fls_check_workspace()
+    fls.fls_forget(blob)
