@@ -221,13 +221,18 @@ __device__ __forceinline__ void store_partial(const OutParams& o, const float4v 
                                              ((nb * kRowBlocks + rb) * 64 + lane) * 16, 0, kAuxCoherent);
 }
 
-// By the wave that called store_partial, once its run is over.
+// A device-scope release in two halves, so that the time the write-back takes can pass behind
+// other work: release_begin right after the stores (the L2 of this XCD starts writing back what
+// it holds), release_end before the flag is raised (waits for that and for every earlier store).
+// Together they are the instruction sequence of a release fence at device scope.  Waiting for the
+// stores alone is not enough: a store counts as done when the XCD's L2 has it, and the flag could
+// reach memory before the data does (seen as a wrong band about once in a thousand calls).
+__device__ __forceinline__ void release_begin() { asm volatile("buffer_wbl2 sc1" ::: "memory"); }
+__device__ __forceinline__ void release_end() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// By the wave that called store_partial (and release_begin behind it), once its run is over.
 __device__ __forceinline__ void publish_partial(const OutParams& o, uint32_t wg, int lane) {
-  // A device-scope release: the L2 of this XCD writes back what it holds and the wave waits for
-  // that.  Waiting for the stores alone (s_waitcnt vmcnt(0)) is not enough: a store counts as done
-  // when the XCD's L2 has it, and the flag could reach memory before the data does (seen as a wrong
-  // band about once in a thousand calls).
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+  release_end();
   if (lane == 0) __hip_atomic_store(o.flags + wg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
@@ -327,6 +332,7 @@ __device__ __forceinline__ void hand_over_piece(const OutParams& o, WgReduceLds<
         st.own_band = band;
       } else {
         store_partial<NB>(o, acc, wg, lane);
+        release_begin();
         st.publish = true;
       }
     }

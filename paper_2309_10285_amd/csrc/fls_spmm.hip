@@ -290,6 +290,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
       hs.own_band = band;
     } else {
       store_partial<NB>(p.out, acc, blockIdx.x, lane);
+      release_begin();
       hs.publish = true;
     }
   };
