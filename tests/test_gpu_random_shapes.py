@@ -72,3 +72,69 @@ def test_random_shape_matches_oracle(oracle_mod, i, M, K, N, beta, mask):
         assert not C.any() and not D.any()
     fls.fls_forget(blob)
     fls.fls_check_workspace()
+
+
+def test_random_call_sequence_on_one_workspace(oracle_mod):
+    """Eight matrices of different shapes, widths and sparsities; 2000 calls drawn at random among them (sparse and
+    dense), back to back on one registered workspace, most of them without waiting in between.  Each matrix's first
+    result is checked against the oracle on sampled bands; every later result must repeat it to within fp16
+    rounding.  Calls of different shapes reuse the same flags, partial-sum slots and repacked-X area, so anything
+    one call leaves behind, or reads before it is there, shows up as a wrong band in another."""
+    import torch
+
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2309_10285_amd as fls
+
+    fls.lib()
+    g = np.random.Generator(np.random.Philox(777))
+    items = []
+    for i in range(8):
+        M = 128 * int(g.integers(8, 200))
+        K = 32 * int(g.integers(8, 400))
+        N = int(g.integers(1, 257))
+        beta = float(g.choice([0.5, 0.7, 0.8, 0.9, 0.95]))
+        W = wl.prune_uniform(wl.gen_weights_f32(M, K, 5000 + i), beta, 6000 + i)
+        X = wl.gen_x(N, K, 7000 + i)
+        Wd = torch.from_numpy(W.view(np.float16)).cuda()
+        Xd = torch.from_numpy(X.view(np.float16)).cuda()
+        blob, _ = fls.fls_compress(Wd)
+        items.append(dict(M=M, K=K, N=N, W=W, X=X, Wd=Wd, Xd=Xd, blob=blob.clone()))
+    fls.fls_forget()
+    fls.ensure_workspace(128 * 200, 32 * 400, 256)
+    for it in items:  # first results, against the oracle
+        M, K, N = it["M"], it["K"], it["N"]
+        for kind in ("spmm", "dense"):
+            C = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+            if kind == "spmm":
+                fls.fls_spmm(it["blob"], it["Xd"], C, M, K, N)
+            else:
+                fls.fls_dense_gemm(it["Wd"], it["Xd"], C, M, K, N)
+            torch.cuda.synchronize()
+            got = C.cpu().numpy()
+            assert not np.isnan(got).any()
+            for band in sorted({0, M // 256, M // 128 - 1}):
+                m0, m1 = band * 128, band * 128 + 128
+                ref = oracle_mod.ref_spmm_f64(it["W"][m0:m1], it["X"])
+                scale = max(float(np.abs(ref).max()), 1e-30)
+                assert float(np.abs(got[:, m0:m1].astype(np.float64) - ref).max()) / scale <= TOL, (kind, band)
+            it[kind] = C.float()
+            it[kind + "_scale"] = max(float(C.float().abs().max()), 1e-30)
+    worst = torch.zeros((), device="cuda")
+    for step in range(2000):
+        it = items[int(g.integers(0, len(items)))]
+        kind = "spmm" if g.random() < 0.8 else "dense"
+        M, K, N = it["M"], it["K"], it["N"]
+        C = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+        if kind == "spmm":
+            fls.fls_spmm(it["blob"], it["Xd"], C, M, K, N)
+        else:
+            fls.fls_dense_gemm(it["Wd"], it["Xd"], C, M, K, N)
+        err = torch.nan_to_num((C.float() - it[kind]).abs(), nan=float("inf")).max() / it[kind + "_scale"]
+        worst = torch.maximum(worst, err)
+        if g.random() < 0.2:
+            torch.cuda.synchronize()
+    assert float(worst) <= TOL
+    fls.fls_check_workspace()
+    assert int(fls._ws_tensor[:512 * 4].cpu().numpy().view(np.uint32).max()) == 0  # every flag is down again
+    fls.fls_forget()
