@@ -118,7 +118,7 @@ __global__ __launch_bounds__(WAVES * 64) void dense_kernel(DenseParams p) {
     tc += WAVES;
     ktc += WAVES;
     if (ktc >= KT || tc >= t1) {  // the wave's next step is in another band, or there is none
-      hand_over_piece<NB>(p.out, red, acc, hs, bandc, piece_tiles, share0, share1, blockIdx.x, lane, false);
+      hand_over_piece<NB>(p.out, red, acc, hs, bandc, piece_tiles, share0, share1, blockIdx.x, lane, false, false);
       piece_tiles = 0;
       while (ktc >= KT) {
         ktc -= KT;

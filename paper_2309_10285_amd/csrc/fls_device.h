@@ -230,8 +230,10 @@ __device__ __forceinline__ void store_partial(const OutParams& o, const float4v 
 __device__ __forceinline__ void release_begin() { asm volatile("buffer_wbl2 sc1" ::: "memory"); }
 __device__ __forceinline__ void release_end() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-// By the wave that called store_partial (and release_begin behind it), once its run is over.
-__device__ __forceinline__ void publish_partial(const OutParams& o, uint32_t wg, int lane) {
+// By the wave that called store_partial, once its run is over; `begun` tells whether it has called
+// release_begin behind the stores already.
+__device__ __forceinline__ void publish_partial(const OutParams& o, uint32_t wg, int lane, bool begun) {
+  if (!begun) release_begin();
   release_end();
   if (lane == 0) __hip_atomic_store(o.flags + wg, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -304,6 +306,7 @@ __device__ __forceinline__ void owner_finish(const OutParams& o, float4v (&acc)[
 // What a wave carries from the tile loop to the end of its run.
 struct HandoverState {
   bool publish = false;  // it stored its workgroup's partial sum and still has to publish it
+  bool released = false; // release_begin has been called behind those stores
   bool own = false;      // it holds the owner's sum of band own_band in its accumulators
   uint32_t own_band = 0;
 };
@@ -314,7 +317,8 @@ struct HandoverState {
 template <int NB>
 __device__ __forceinline__ void hand_over_piece(const OutParams& o, WgReduceLds<NB>* red, float4v (&acc)[kRowBlocks][NB],
                                                 HandoverState& st, uint32_t band, uint32_t tiles, uint32_t share0,
-                                                uint32_t share1, uint32_t wg, int lane, bool local_only) {
+                                                uint32_t share1, uint32_t wg, int lane, bool local_only,
+                                                bool early_release) {
   const uint32_t seq = band - share0 / o.KT;
   if (tiles == o.KT) {
     store_band<NB>(o, acc, band, lane);  // this wave alone saw the whole band
@@ -332,7 +336,13 @@ __device__ __forceinline__ void hand_over_piece(const OutParams& o, WgReduceLds<
         st.own_band = band;
       } else {
         store_partial<NB>(o, acc, wg, lane);
-        release_begin();
+        // the sparse kernel's load ring is empty at the end of a piece, so nothing of it has to be
+        // waited for to start the write-back here; the dense kernel keeps its ring going and
+        // releases in one go at the end
+        if (early_release) {
+          release_begin();
+          st.released = true;
+        }
         st.publish = true;
       }
     }
@@ -351,7 +361,7 @@ __device__ __forceinline__ void hand_over_finish(const OutParams& o, float4v (&a
                                                  const HandoverState& st, uint32_t wg, uint32_t P, int lane) {
   if (st.publish) {
     FLS_STAMP(o.flags, wg, 3);
-    publish_partial(o, wg, lane);
+    publish_partial(o, wg, lane, st.released);
     FLS_STAMP(o.flags, wg, 4);
   }
   if (st.own) {

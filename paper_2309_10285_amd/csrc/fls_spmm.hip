@@ -213,7 +213,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     } else if (FLS_ABLATE & 128) {
       store_band<NB>(p.out, acc, band, lane);
     } else {
-      hand_over_piece<NB>(p.out, red, acc, hs, band, tiles, share0, share1, blockIdx.x, lane, (FLS_ABLATE & 64) != 0);
+      hand_over_piece<NB>(p.out, red, acc, hs, band, tiles, share0, share1, blockIdx.x, lane, (FLS_ABLATE & 64) != 0, true);
     }
     if (FLS_ABLATE & (1 | 128)) {
 #pragma unroll
@@ -291,6 +291,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     } else {
       store_partial<NB>(p.out, acc, blockIdx.x, lane);
       release_begin();
+      hs.released = true;
       hs.publish = true;
     }
   };
