@@ -325,16 +325,16 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 
 // ---------------------------------------------------------------- host launcher
 
-#ifndef FLS_NSTAGE
-#define FLS_NSTAGE 3
-#endif
 
-// Tiles in flight per wave.  What has to be kept in flight is bytes, not tiles: about 10 KB per
-// wave (80 KB per CU) covers the latency of HBM, so sparser matrices (fewer rounds R of 256 words
-// per tile) get a deeper ring, as far as the registers allow: a stage costs 4 R + 4 NB registers,
-// the accumulators 32 NB, and a wave has 256 registers with eight waves per workgroup, 512 with four.
+// Tiles in flight per wave: set by measurement.  One column block per wave: two tiles ahead up to
+// 1024 words per tile (about 8 KB per wave, 64 KB per CU in flight), three for denser tiles; a
+// deeper ring measured slower (C2 with two / three / four tiles: 33.7 / 35.5 / 35.8 us).  A stage
+// costs 4 R + 4 NB registers, the accumulators 32 NB, and a wave has 256 registers.
 constexpr int ring_depth(int NB, int WAVES, int R) {
+#ifdef FLS_NSTAGE
   if (NB == 1) return FLS_NSTAGE;
+#endif
+  if (NB == 1) return R <= 4 ? 2 : 3;  // measured: two tiles ahead beat three up to 1024 words per tile (C2 35.5 -> 33.7 us)
   return R <= 2 ? 4 : 2;
 }
 
