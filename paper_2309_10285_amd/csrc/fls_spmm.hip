@@ -326,16 +326,16 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 // ---------------------------------------------------------------- host launcher
 
 
-// Tiles in flight per wave: set by measurement.  One column block per wave: two tiles ahead up to
-// 1024 words per tile (about 8 KB per wave, 64 KB per CU in flight), three for denser tiles; a
-// deeper ring measured slower (C2 with two / three / four tiles: 33.7 / 35.5 / 35.8 us).  A stage
-// costs 4 R + 4 NB registers, the accumulators 32 NB, and a wave has 256 registers.
+// Tiles in flight per wave: set by measurement.  Two tiles ahead (about 8 KB per wave, 64 KB per CU
+// in flight at 1024 words per tile) everywhere but one column block per wave with tiles of more
+// than 1024 words, where three were 1 % faster; deeper rings measured slower (C2 with two / three /
+// four tiles: 33.7 / 35.5 / 35.8 us; 28672 x 7168 at 90 %, 32 columns, two / four: 30.3 / 31.3 us).
+// A stage costs 4 R + 4 NB registers, the accumulators 32 NB, and a wave has 256 registers.
 constexpr int ring_depth(int NB, int WAVES, int R) {
 #ifdef FLS_NSTAGE
   if (NB == 1) return FLS_NSTAGE;
 #endif
-  if (NB == 1) return R <= 4 ? 2 : 3;  // measured: two tiles ahead beat three up to 1024 words per tile (C2 35.5 -> 33.7 us)
-  return R <= 2 ? 4 : 2;
+  return NB == 1 && R > 4 ? 3 : 2;
 }
 
 template <int NB, int WAVES, int R>
