@@ -280,7 +280,7 @@ def main():
         "host_ms_per_step": round(host_ms, 5),
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
-                     "kernel": "fls::spmm_kernel" if N <= 32 or st["max_tile_words"] > 2048 else "fls::xpack_kernel + fls::spmm_wide_kernel + fls::wide_reduce_kernel", "algorithmic_bytes_per_launch": alg_bytes,
+                     "kernel": "fls::spmm_kernel" if N <= 32 or st["max_tile_words"] > 2560 else "fls::xpack_kernel + fls::spmm_wide_kernel + fls::wide_reduce_kernel", "algorithmic_bytes_per_launch": alg_bytes,
                      "avg_launch_us": round(ms * 1e3, 3)},
     }
 

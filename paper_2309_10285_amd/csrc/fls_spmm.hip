@@ -385,9 +385,10 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
   else if (a.max_tile_words <= 3 * 256) R = 3;
   else if (a.max_tile_words <= 4 * 256) R = 4;
   else if (a.max_tile_words <= 6 * 256) R = 6;
-  // The 64-column pass stages at most 2048 words of a tile (it has no slow path for more): a
-  // matrix with denser tiles - less than half sparse somewhere - takes 32-column passes throughout.
-  const bool wide_ok = a.max_tile_words <= 8 * 256;
+  // The 64-column pass stages at most 2560 words of a tile (it has no slow path for more; twelve
+  // rounds of 256 no longer fit its registers): a matrix with denser tiles - less than 40 % sparse
+  // somewhere - takes 32-column passes throughout.
+  const bool wide_ok = a.max_tile_words <= 10 * 256;
   if (a.N > kGroupCols && wide_ok) {
     hipError_t e = launch_xpack(a.X, a.xpack, a.K, a.N, stream);  // the 64-column passes read X from a copy in fragment order
     if (e != hipSuccess) return e;

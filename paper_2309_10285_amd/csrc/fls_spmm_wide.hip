@@ -389,7 +389,8 @@ hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, hipStream_t stream
   else if (a.max_tile_words <= 3 * 256) e = launch_wide_variant<3, 8, 4>(p, grid, stream);
   else if (a.max_tile_words <= 4 * 256) e = launch_wide_variant<4, 8, 4>(p, grid, stream);
   else if (a.max_tile_words <= 6 * 256) e = launch_wide_variant<6, 4, 4>(p, grid, stream);
-  else e = launch_wide_variant<8, 4, 4>(p, grid, stream);
+  else if (a.max_tile_words <= 8 * 256) e = launch_wide_variant<8, 4, 4>(p, grid, stream);
+  else e = launch_wide_variant<10, 4, 4>(p, grid, stream);
   if (e != hipSuccess) return e;
   if (p.S > 1) e = launch_wide_reduce(p, stream);
   return e;

@@ -82,6 +82,8 @@ def _cases():
         # longest tile between 512 and 768 words, and between 1024 and 1536: the three- and six-round rings
         ("uniform-87", 1024, 1024, 0.87, "uniform"),
         ("uniform-68", 768, 1024, 0.68, "uniform"),
+        # longest tile between 2048 and 2560 words: the ten-round ring of the 64-column pass
+        ("uniform-45", 512, 1024, 0.45, "uniform"),
     ]:
         W32 = wl.gen_weights_f32(M, K, int(g.integers(1 << 30)))
         if mask == "uniform":
