@@ -24,7 +24,7 @@ MIN_ROTATION_BYTES = 1 << 30
 
 # HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE scaled by a copy
 # kernel of known size); filled from profiles/ for the workloads that were profiled, else null.
-MEASURED_TRAFFIC_BYTES = {"C2": 169.94e6}  # profiles/spmm_C2_hbm_traffic.md
+MEASURED_TRAFFIC_BYTES = {"C2": 169.94e6, "C4": 342.1e6}  # profiles/spmm_C2_hbm_traffic.md, spmm_C4_hbm_traffic.md
 
 
 def _time_loop(calls, steps, warmup):
