@@ -1,11 +1,17 @@
 """Benchmark of the Load-as-Sparse / Compute-as-Dense SpMM hot path on one MI355X.
 
-One "step" = one fls_spmm call over the OPT-30B-shaped FFN up-projection (W 28672 x 7168 fp16,
-magnitude-pruned to 80 %, X 7168 x 16), inputs resident in HBM.  Steps rotate over several
-copies of the compressed matrix so that no step finds its weights in the 256 MB Infinity Cache.
-Prints ONE JSON line: metric/value (dense-equivalent TFLOP/s), the roofline object of the SpMM kernel (algorithmic
-bytes per launch / measured launch time against the 8 TB/s HBM peak, measured HBM traffic), the own dense GEMM on the
-unpruned matrix, the CPU oracle timed on the host cores, and the parity of C against that oracle.
+One "step" = one fls_spmm call over the headline workload, the OPT-175B-shaped FFN down-projection
+(W 12288 x 49152 fp16, magnitude-pruned to 90 %, X 49152 x 64: the largest named configuration),
+inputs resident in HBM.  Steps rotate over several copies of the compressed matrix so that no step
+finds its weights in the 256 MB Infinity Cache.  Prints ONE JSON line: metric/value (dense-equivalent
+TFLOP/s), the roofline object (algorithmic bytes per call / measured time of a call against the larger of
+the HBM and the MFMA lower bound), the empirical ceiling of a plain streaming read of the same blob, the
+own dense GEMM on the unpruned matrix, the CPU oracle timed on the host cores over the whole workload, and
+the parity of the whole of C against that oracle; the other named configurations (C2, C3) follow under
+"other_configs" with the same objects.  Exits non-zero if any C is off the oracle by more than 2e-3.
+
+The oracle is imported by the cpu_baseline / parity leg of the bench line and by the parity checks of
+--sweep and --layer; nothing that is timed touches it.
 """
 import argparse
 import json
@@ -22,9 +28,17 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 MIN_ROTATION_BYTES = 1 << 30
 
-# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE scaled by a copy
-# kernel of known size); filled from profiles/ for the workloads that were profiled, else null.
-MEASURED_TRAFFIC_BYTES = {"C2": 169.94e6, "C4": 342.1e6}  # profiles/spmm_C2_hbm_traffic.md, spmm_C4_hbm_traffic.md
+PARITY_TOL = 2e-3
+HEADLINE = "C4"         # the largest named configuration that fits one GPU (604 M weights, 77 GFLOP per call)
+OTHERS = ("C2", "C3")   # reported beside it in the same JSON line
+
+# HBM traffic per call.  It cannot be read inside this process: it comes from separate rocprofv3 --pmc runs
+# of this script (FETCH_SIZE, then WRITE_SIZE, scaled by a copy kernel of known size), whose summaries are
+# under profiles/; the line carries the figure together with the file it was copied from, or null.
+MEASURED_TRAFFIC = {
+    "C2": (169.94e6, "profiles/spmm_C2_hbm_traffic.md (separate rocprofv3 --pmc runs, not this run)"),
+    "C4": (342.1e6, "profiles/spmm_C4_hbm_traffic.md (separate rocprofv3 --pmc runs, not this run)"),
+}
 
 
 def _time_loop(calls, steps, warmup):
@@ -71,7 +85,6 @@ def run_sweep(args):
     fls.lib()
     M, K = wl.SWEEP_M, wl.SWEEP_K
     W32 = wl.gen_weights_f32(M, K, wl.SWEEP_SEED)
-    rows = 256  # rows of C checked against the oracle at every point
     out = open(args.out, "w") if args.out else None
 
     def emit(rec):
@@ -110,15 +123,14 @@ def run_sweep(args):
             for N in wl.SWEEP_NS:
                 C = torch.empty((N, M), dtype=torch.float16, device="cuda")
                 ms, _ = _time_loop([fls.prepare_spmm(b, Xd[N], C, M, K, N) for b in blobs], args.steps, args.warmup)
-                ref = oracle.ref_spmm_f64(Wb, Xs[N], rows=(0, rows))
-                got = C.cpu().numpy()[:, :rows].astype(np.float64)
-                err = float(np.abs(got - ref[:, :rows]).max() / np.abs(ref[:, :rows]).max())
+                ref = oracle.ref_spmm_f64(Wb, Xs[N])  # the whole of C
+                err = float(np.abs(C.cpu().numpy().astype(np.float64) - ref).max() / np.abs(ref).max())
                 alg = st["bytes_total"] + 2 * K * N + 2 * M * N
                 emit({"point": f"{mask}-{int(round(beta * 100))}-N{N}", "mask": mask, "sparsity": beta, "N": N,
                       "nnz": st["nnz"], "max_tile_words": st["max_tile_words"], "us": round(ms * 1e3, 2),
                       "TFLOPs": round(2.0 * M * K * N / ms / 1e9, 1), "GBps": round(alg / ms / 1e6, 1),
                       "hbm_frac": round(alg / ms / 1e6 / HBM_PEAK_GBS, 4), "speedup_vs_dense": round(dense_ms[N] / ms, 3),
-                      "max_rel_err_first_256_rows": err, "parity_ok": err <= 2e-3})
+                      "max_rel_err_whole_c": err, "parity_ok": err <= 2e-3})
                 worst = max(worst, err)
             # the copies' memory goes back to torch's allocator and will hold other blobs: the library must
             # not keep the headers it remembers for these addresses
@@ -154,12 +166,12 @@ def _run_layer_on_stream(args, torch, wl, fls, side):
         if not args.no_cpu_baseline:
             import oracle
 
-            ref = oracle.ref_spmm_f64(Wb, Xb, rows=(0, 256))[:, :256]
-            err = float(np.abs(C.cpu().numpy()[:, :256].astype(np.float64) - ref).max() / np.abs(ref).max())
+            ref = oracle.ref_spmm_f64(Wb, Xb)  # the whole of C
+            err = float(np.abs(C.cpu().numpy().astype(np.float64) - ref).max() / np.abs(ref).max())
         alg = st["bytes_total"] + 2 * cfg.K * N + 2 * cfg.M * N
         recs.append({"matmul": cfg.what, "M": cfg.M, "K": cfg.K, "nnz": st["nnz"], "alone_us": round(ms * 1e3, 2),
                      "alone_GBps": round(alg / ms / 1e6, 1), "dense_alone_us": round(dms * 1e3, 2),
-                     "algorithmic_bytes": alg, "max_rel_err_first_256_rows": err})
+                     "algorithmic_bytes": alg, "max_rel_err_whole_c": err})
 
     def layer_calls(table):
         return [lambda c=c, table=table: [calls[c]() for calls in table] for c in range(copies)]
@@ -207,13 +219,144 @@ def run_layer(args):
     print(json.dumps(out), flush=True)
 
 
+MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X published dense fp16 matrix rate
+
+
+def measure_config(name, args, with_dense, with_cpu):
+    """Times fls_spmm on one named configuration (inputs resident in HBM, weights rotated over more than 1 GB of
+    copies), the streaming-read ceiling over the same blobs, optionally the dense pair; checks the whole of C
+    against the oracle (that pass is also the cpu_baseline).  Returns a dict of results."""
+    import torch
+
+    import fls_workloads as wl
+    import paper_2309_10285_amd as fls
+    from paper_2309_10285_amd import stream_probe
+
+    cfg = wl.CONFIGS[name]
+    M, K, N = cfg.M, cfg.K, cfg.N
+    t_gen = time.perf_counter()
+    W32 = wl.make_w32(cfg)
+    Wb, Xb = wl.make_inputs(cfg, W32)
+    t_gen = time.perf_counter() - t_gen
+
+    X = torch.from_numpy(Xb.view(np.float16)).cuda()
+    W = torch.from_numpy(Wb.view(np.float16)).cuda()
+    blob0, st = fls.fls_compress(W)
+    blob0 = blob0.clone()  # trimmed copy; the bound-sized buffer is released
+    del W
+    n_copies = max(2, -(-MIN_ROTATION_BYTES // st["bytes_total"]))
+    blobs = [blob0] + [blob0.clone() for _ in range(n_copies - 1)]
+    fls.ensure_workspace(M, K, N)
+    C = torch.empty((N, M), dtype=torch.float16, device="cuda")
+
+    ms, host_ms = _time_loop([fls.prepare_spmm(b, X, C, M, K, N) for b in blobs], args.steps, args.warmup)
+    flops = 2.0 * M * K * N
+    alg_bytes = st["bytes_total"] + 2 * K * N + 2 * M * N  # blob + X + C
+    tflops = flops / (ms * 1e-3) / 1e12
+    gbs = alg_bytes / (ms * 1e-3) / 1e9
+    C_host = C.cpu().numpy()
+    fls.fls_check_workspace()
+
+    # which roof: the larger of the two lower bounds on the time of a call
+    t_hbm_us = alg_bytes / (HBM_PEAK_GBS * 1e3)
+    t_mfma_us = flops / (MFMA_F16_PEAK_TFLOPS * 1e6)
+    narrow = N <= 32 or st["max_tile_words"] > 2560
+    kernels = "fls::spmm_kernel" if narrow else "fls::xpack_kernel + fls::spmm_wide_kernel + fls::wide_reduce_kernel"
+    traffic = MEASURED_TRAFFIC.get(name)
+    res = {
+        "name": name, "cfg": cfg, "st": st, "n_copies": n_copies, "ms": ms, "host_ms": host_ms, "tflops": tflops,
+        "gbs": gbs, "alg_bytes": alg_bytes, "t_gen": t_gen,
+        "roofline": {"bound": "hbm" if t_hbm_us >= t_mfma_us else "mfma",
+                     "achieved": round(gbs, 1) if t_hbm_us >= t_mfma_us else round(tflops, 1),
+                     "peak": HBM_PEAK_GBS if t_hbm_us >= t_mfma_us else MFMA_F16_PEAK_TFLOPS,
+                     "unit": "GB/s" if t_hbm_us >= t_mfma_us else "TFLOP/s",
+                     "frac": round(max(t_hbm_us, t_mfma_us) / (ms * 1e3), 4),
+                     "traffic": traffic[0] if traffic else None,
+                     "traffic_source": traffic[1] if traffic else None,
+                     "kernel": kernels, "algorithmic_bytes_per_launch": alg_bytes,
+                     "avg_launch_us": round(ms * 1e3, 3),
+                     "roof_us": {"hbm_8TBps": round(t_hbm_us, 2), "mfma_f16_2.5PFLOPs": round(t_mfma_us, 2)}},
+    }
+
+    # the empirical ceiling: a plain streaming read of the same blobs (no LDS, no MFMA, nothing stored), with as
+    # many workgroups as the kernel uses when it runs one per band, and with one per CU
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    bands = M // fls.TILE_M
+    grids = sorted({cus, bands * (cus // bands) if bands <= cus else cus})
+    probe_steps = max(20, min(args.steps, 400))
+    ceiling = {"what": "plain 16 B non-temporal read of the blob, 8 waves per workgroup, 2 x 8 loads in flight per lane",
+               "bytes": st["bytes_total"]}
+    best = 0.0
+    for g in grids:
+        rate, us = stream_probe.stream_read_gbps(blobs, g, unroll=8, steps=probe_steps, warmup=20)
+        ceiling[f"grid_{g}"] = {"GBps": round(rate, 1), "us": round(us, 2)}
+        best = max(best, rate)
+    ceiling["GBps"] = round(best, 1)
+    ceiling["kernel_vs_ceiling"] = round(gbs / best, 4)
+    res["stream_ceiling"] = ceiling
+
+    if with_dense:
+        Wd = torch.from_numpy(wl.dense_bits(W32).view(np.float16)).cuda()
+        n_d = max(2, -(-MIN_ROTATION_BYTES // (2 * M * K)))
+        dense = [Wd] + [Wd.clone() for _ in range(n_d - 1)]
+        D = torch.empty((N, M), dtype=torch.float16, device="cuda")
+        dms, _ = _time_loop([fls.prepare_dense_gemm(w, X, D, M, K, N) for w in dense], args.steps, args.warmup)
+        dbytes = 2 * M * K + 2 * K * N + 2 * M * N
+        res["dense_gemm"] = {"ms_per_step": round(dms, 5), "TFLOPs": round(flops / (dms * 1e-3) / 1e12, 2),
+                             "achieved_GBps": round(dbytes / (dms * 1e-3) / 1e9, 1),
+                             "hbm_frac": round(dbytes / (dms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                             "spmm_speedup": round(dms / ms, 3), "copies_rotated": n_d}
+        # context only: the vendor library's GEMM on the same operands and layouts (the paper's dense baseline is
+        # the vendor library, Sec. 6.1), through torch.matmul (rocBLAS / hipBLASLt); C[N, M] = X[N, K] . W[M, K]^T
+        V = torch.empty((N, M), dtype=torch.float16, device="cuda")
+        vms, _ = _time_loop([lambda w=w: torch.matmul(X, w.t(), out=V) for w in dense], args.steps, args.warmup)
+        res["vendor_gemm"] = {"library": "torch.matmul (rocBLAS / hipBLASLt)", "ms_per_step": round(vms, 5),
+                              "achieved_GBps": round(dbytes / (vms * 1e-3) / 1e9, 1), "spmm_speedup": round(vms / ms, 3)}
+        del dense, Wd, D, V
+    del W32
+
+    if with_cpu:
+        import oracle  # the cpu_baseline leg is the only part of the bench line that touches the oracle
+
+        # the oracle over the whole workload (every row of C), timed; repeated while it is short, up to about
+        # ten seconds of CPU work
+        t0 = time.perf_counter()
+        ref = oracle.ref_spmm_f64(Wb, Xb)
+        dt = time.perf_counter() - t0
+        reps = int(max(1, min(50, 10.0 // max(dt, 1e-3))))
+        if reps > 1:
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                ref = oracle.ref_spmm_f64(Wb, Xb)
+            dt = (time.perf_counter() - t0) / reps
+        scale = float(np.abs(ref).max())
+        err = float(np.abs(C_host.astype(np.float64) - ref).max()) / scale
+        res["cpu_baseline"] = {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s",
+                               "cores": oracle.ref_threads(), "kind": "oracle",
+                               "sample": f"the whole workload: W ({M}x{K}) x X ({K}x{N}), fp64 triple loop, zeros not "
+                                         f"skipped, {dt:.3f} s per pass, mean of {reps} passes"}
+        res["parity"] = {"max_rel_err_vs_oracle": err, "rows_checked": M, "tolerance": PARITY_TOL,
+                         "ok": bool(err <= PARITY_TOL)}
+    for b in blobs:
+        fls.fls_forget(b)
+    return res
+
+
+def _workload_text(cfg, st):
+    return (f"{cfg.name}: {cfg.what}; W {cfg.M}x{cfg.K} fp16 N(0,0.02) {cfg.mask}-pruned to "
+            f"{int(cfg.beta * 100)} % sparsity, X {cfg.K}x{cfg.N} fp16 N(0,1)")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # a step is ~40 us: the defaults keep the GPU busy long enough (tens of ms) for its clocks to settle
+    # a step is 30 - 90 us: the defaults keep the GPU busy long enough (tens of ms) for its clocks to settle
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--config", default="C2", help="C1..C4 (C2 is the configuration the metric is quoted on), L1, L2 (OPT-175B-sized)")
+    ap.add_argument("--config", default=HEADLINE,
+                    help=f"C1..C4, L1, L2 (OPT-175B-sized); default {HEADLINE}, the largest named single-GPU configuration")
+    ap.add_argument("--no-others", action="store_true",
+                    help="leave out the other named configurations (C2, C3) that the default run reports beside the headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--sweep", action="store_true",
@@ -239,50 +382,30 @@ def main():
 
     import torch
 
-    import fls_workloads as wl
     import paper_2309_10285_amd as fls
 
     fls.lib()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    cfg = wl.CONFIGS[args.config]
-    M, K, N = cfg.M, cfg.K, cfg.N
-    t_gen = time.perf_counter()
-    W32 = wl.make_w32(cfg)
-    Wb, Xb = wl.make_inputs(cfg, W32)
-    t_gen = time.perf_counter() - t_gen
 
-    X = torch.from_numpy(Xb.view(np.float16)).cuda()
-    W = torch.from_numpy(Wb.view(np.float16)).cuda()
-    blob0, st = fls.fls_compress(W)
-    blob0 = blob0.clone()  # trimmed copy; the bound-sized buffer is released
-    n_copies = max(2, -(-MIN_ROTATION_BYTES // st["bytes_total"]))
-    blobs = [blob0] + [blob0.clone() for _ in range(n_copies - 1)]
-    fls.ensure_workspace(M, K, N)
-    C = torch.empty((N, M), dtype=torch.float16, device="cuda")
-
-    ms, host_ms = _time_loop([fls.prepare_spmm(b, X, C, M, K, N) for b in blobs], args.steps, args.warmup)
-    flops = 2.0 * M * K * N
-    alg_bytes = st["bytes_total"] + 2 * K * N + 2 * M * N  # blob + X + C
-    tflops = flops / (ms * 1e-3) / 1e12
-    gbs = alg_bytes / (ms * 1e-3) / 1e9
-    C_host = C.cpu().numpy()
-
+    r = measure_config(args.config, args, with_dense=not args.no_dense, with_cpu=not args.no_cpu_baseline)
+    cfg, st = r["cfg"], r["st"]
     out = {
-        "metric": f"SpMM dense-equivalent TFLOP/s (2*M*K*N / latency), {cfg.what}, {int(cfg.beta * 100)} % sparsity, N={N}",
-        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "metric": f"SpMM dense-equivalent TFLOP/s (2*M*K*N / latency), {cfg.what}, {int(cfg.beta * 100)} % sparsity, N={cfg.N}",
+        "value": round(r["tflops"], 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(r["ms"], 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: {cfg.what}; W {M}x{K} fp16 N(0,0.02) {cfg.mask}-pruned to "
-                               f"{int(cfg.beta * 100)} % sparsity, X {K}x{N} fp16 N(0,1)",
-                   "M": M, "K": K, "N": N, "sparsity": cfg.beta, "nnz": st["nnz"], "blob_bytes": st["bytes_total"],
-                   "blob_copies_rotated": n_copies, "seed": cfg.seed},
-        "achieved_GBps": round(gbs, 1), "hbm_frac": round(gbs / HBM_PEAK_GBS, 4),
-        "host_ms_per_step": round(host_ms, 5),
-        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
-                     "kernel": "fls::spmm_kernel" if N <= 32 or st["max_tile_words"] > 2560 else "fls::xpack_kernel + fls::spmm_wide_kernel + fls::wide_reduce_kernel", "algorithmic_bytes_per_launch": alg_bytes,
-                     "avg_launch_us": round(ms * 1e3, 3)},
+        "config": {"workload": _workload_text(cfg, st),
+                   "M": cfg.M, "K": cfg.K, "N": cfg.N, "sparsity": cfg.beta, "nnz": st["nnz"], "blob_bytes": st["bytes_total"],
+                   "blob_copies_rotated": r["n_copies"], "seed": cfg.seed},
+        "achieved_GBps": round(r["gbs"], 1), "hbm_frac": round(r["gbs"] / HBM_PEAK_GBS, 4),
+        "host_ms_per_step": round(r["host_ms"], 5),
+        "roofline": r["roofline"], "stream_ceiling": r["stream_ceiling"],
     }
+    for key in ("dense_gemm", "vendor_gemm", "cpu_baseline", "parity"):
+        if key in r:
+            out[key] = r[key]
+    gen_s = r["t_gen"]
+    failed = [args.config] if "parity" in r and not r["parity"]["ok"] else []
 
     if args.calibration_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
@@ -292,54 +415,26 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    if not args.no_dense:
-        Wd = torch.from_numpy(wl.dense_bits(W32).view(np.float16)).cuda()
-        n_d = max(2, -(-MIN_ROTATION_BYTES // (2 * M * K)))
-        dense = [Wd] + [Wd.clone() for _ in range(n_d - 1)]
-        D = torch.empty((N, M), dtype=torch.float16, device="cuda")
-        dms, _ = _time_loop([fls.prepare_dense_gemm(w, X, D, M, K, N) for w in dense], args.steps, args.warmup)
-        dbytes = 2 * M * K + 2 * K * N + 2 * M * N
-        out["dense_gemm"] = {"ms_per_step": round(dms, 5), "TFLOPs": round(flops / (dms * 1e-3) / 1e12, 2),
-                             "achieved_GBps": round(dbytes / (dms * 1e-3) / 1e9, 1),
-                             "hbm_frac": round(dbytes / (dms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                             "spmm_speedup": round(dms / ms, 3), "copies_rotated": n_d}
-        # context only: the vendor library's GEMM on the same operands and layouts (the paper's dense baseline is
-        # the vendor library, Sec. 6.1), through torch.matmul (rocBLAS / hipBLASLt); C[N, M] = X[N, K] . W[M, K]^T
-        V = torch.empty((N, M), dtype=torch.float16, device="cuda")
-        vms, _ = _time_loop([lambda w=w: torch.matmul(X, w.t(), out=V) for w in dense], args.steps, args.warmup)
-        out["vendor_gemm"] = {"library": "torch.matmul (rocBLAS / hipBLASLt)", "ms_per_step": round(vms, 5),
-                              "achieved_GBps": round(dbytes / (vms * 1e-3) / 1e9, 1), "spmm_speedup": round(vms / ms, 3)}
-        del dense, Wd
-
-    if not args.no_cpu_baseline:
-        import oracle  # the cpu_baseline leg is the only part of the bench that touches the oracle
-
-        rows = min(M, 4096)
-        t0 = time.perf_counter()
-        ref = oracle.ref_spmm_f64(Wb, Xb, rows=(0, rows))
-        dt = time.perf_counter() - t0
-        # grow the sample until it is a few seconds of CPU work (bounded)
-        while dt < 4.0 and rows < M:
-            rows = min(M, rows * 4)
-            t0 = time.perf_counter()
-            ref = oracle.ref_spmm_f64(Wb, Xb, rows=(0, rows))
-            dt = time.perf_counter() - t0
-        reps = 1
-        if rows == M:  # the whole workload is still short: repeat it up to about ten seconds of CPU work
-            reps = int(max(1, min(50, 10.0 // max(dt, 1e-3))))
-            t0 = time.perf_counter()
-            for _ in range(reps):
-                ref = oracle.ref_spmm_f64(Wb, Xb, rows=(0, rows))
-            dt = (time.perf_counter() - t0) / reps
-        scale = float(np.abs(ref[:, :rows]).max())
-        err = float(np.abs(C_host[:, :rows].astype(np.float64) - ref[:, :rows]).max()) / scale
-        out["cpu_baseline"] = {"value": round(2.0 * rows * K * N / dt / 1e12, 5), "unit": "TFLOP/s",
-                               "cores": oracle.ref_threads(), "kind": "oracle",
-                               "sample": f"rows 0..{rows} of W ({rows}x{K}) x X, fp64 triple loop, zeros not skipped, "
-                                         f"{dt:.3f} s per pass, mean of {reps} passes"}
-        out["parity"] = {"max_rel_err_vs_oracle": err, "rows_checked": rows, "tolerance": 2e-3}
-    out["input_generation_s"] = round(t_gen, 2)
+    if args.config == HEADLINE and not args.no_others:
+        # the other named configurations, each with its own roofline, ceiling, dense pair and parity
+        others = {}
+        for name in OTHERS:
+            o = measure_config(name, args, with_dense=not args.no_dense, with_cpu=not args.no_cpu_baseline)
+            rec = {"workload": _workload_text(o["cfg"], o["st"]), "ms_per_step": round(o["ms"], 5),
+                   "TFLOPs": round(o["tflops"], 2), "achieved_GBps": round(o["gbs"], 1), "roofline": o["roofline"],
+                   "stream_ceiling": o["stream_ceiling"], "nnz": o["st"]["nnz"], "blob_bytes": o["st"]["bytes_total"]}
+            for key in ("dense_gemm", "vendor_gemm", "parity"):
+                if key in o:
+                    rec[key] = o[key]
+            if "parity" in o and not o["parity"]["ok"]:
+                failed.append(name)
+            gen_s += o["t_gen"]
+            others[name] = rec
+        out["other_configs"] = others
+    out["input_generation_s"] = round(gen_s, 2)
     print(json.dumps(out))
+    if failed:
+        sys.exit(f"bench.py: C is off the oracle by more than {PARITY_TOL} on {', '.join(failed)}")
 
 
 if __name__ == "__main__":

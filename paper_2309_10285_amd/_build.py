@@ -6,6 +6,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libfls.so")
 SOURCES = ["fls_api.hip", "fls_spmm.hip", "fls_spmm_wide.hip", "fls_dense.hip", "fls_compress.hip"]
+# measurement code (a plain streaming read: bench.py's empirical ceiling), a library of its own, not part of the C ABI
+PROBE_SOURCE = "fls_stream_probe.hip"
+PROBE_LIB = os.path.join(_HERE, "libfls_probe.so")
 HEADERS = ["fls_device.h", "fls_launch.h", "fls_tile.h", os.path.join("..", "..", "include", "fls.h")]
 
 HIPCC_FLAGS = [
@@ -18,6 +21,8 @@ HIPCC_FLAGS = [
 def build(force=True, verbose=False):
     """Compile every source to an object (in parallel) and link the shared library."""
     objs, procs = [], []
+    probe_cmd = ["hipcc", *HIPCC_FLAGS, "-shared", "-o", PROBE_LIB, os.path.join(CSRC, PROBE_SOURCE)]
+    probe = subprocess.Popen(probe_cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     for src in SOURCES:
         obj = os.path.join(CSRC, src.replace(".hip", ".o"))
         objs.append(obj)
@@ -30,6 +35,9 @@ def build(force=True, verbose=False):
             raise RuntimeError("hipcc failed: " + " ".join(cmd) + "\n" + out)
         if verbose and out.strip():
             print(out)
+    out, _ = probe.communicate()
+    if probe.returncode != 0:
+        raise RuntimeError("hipcc failed: " + " ".join(probe_cmd) + "\n" + out)
     link = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     r = subprocess.run(link, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:

@@ -42,10 +42,23 @@ VARIANTS = [
 ]
 
 
+# the sources that know FLS_ABLATE; the other objects of a variant are the library's own
+ABLATED_SOURCES = ("fls_spmm.hip", "fls_spmm_wide.hip")
+# builds that __graft_entry__.build() keeps beside the library for the GPU test of this tool
+PREBUILT_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "ablate_builds")
+PREBUILT_MASKS = (0, 1 | 2 | 4 | 8 | 16)
+
+
 def build_variant(mask, folder):
+    """libfls_ablate<mask>.so in `folder`: the two kernel sources compiled with -DFLS_ABLATE=<mask>, linked with
+    the library's other objects (built by _build.build(); built here if missing)."""
+    os.makedirs(folder, exist_ok=True)
     lib = os.path.join(folder, f"libfls_ablate{mask}.so")
+    others = [os.path.join(_build.CSRC, s.replace(".hip", ".o")) for s in _build.SOURCES if s not in ABLATED_SOURCES]
+    if not all(os.path.exists(o) for o in others):
+        _build.build()
     objs, procs = [], []
-    for src in _build.SOURCES:
+    for src in ABLATED_SOURCES:
         obj = os.path.join(folder, f"a{mask}_{src.replace('.hip', '.o')}")
         objs.append(obj)
         cmd = ["hipcc", *_build.HIPCC_FLAGS, f"-DFLS_ABLATE={mask}", "-c", os.path.join(_build.CSRC, src), "-o", obj]
@@ -54,19 +67,41 @@ def build_variant(mask, folder):
         _, err = p.communicate()
         if p.returncode != 0:
             raise RuntimeError(err)
-    subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs], check=True)
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs, *others], check=True)
     for o in objs:
         os.remove(o)
     return lib
 
 
-def time_variant(lib_path, blobs, X, C, M, K, N, ws, steps, warmup):
-    import torch
-
+def _bind(lib_path):
     L = ctypes.CDLL(lib_path)
     vp, i64 = ctypes.c_void_p, ctypes.c_int64
     L.fls_spmm.argtypes = [vp, vp, vp, i64, i64, i64, vp]
     L.fls_set_workspace.argtypes = [vp, ctypes.c_size_t, vp]
+    L.fls_check_workspace.argtypes = [vp]
+    return L
+
+
+def run_once(lib_path, blob, X, C, M, K, N, ws):
+    """One fls_spmm call through the build at lib_path (its own workspace registration), waited for.
+    Returns the error code of the call, or of the workspace check after it."""
+    import torch
+
+    L = _bind(lib_path)
+    vp = ctypes.c_void_p
+    stream = vp(torch.cuda.current_stream().cuda_stream)
+    rc = L.fls_set_workspace(vp(ws.data_ptr()), ws.numel(), stream)
+    if rc == 0:
+        rc = L.fls_spmm(vp(blob.data_ptr()), vp(X.data_ptr()), vp(C.data_ptr()), M, K, N, stream)
+    torch.cuda.synchronize()
+    return rc if rc != 0 else L.fls_check_workspace(stream)
+
+
+def time_variant(lib_path, blobs, X, C, M, K, N, ws, steps, warmup):
+    import torch
+
+    L = _bind(lib_path)
+    vp = ctypes.c_void_p
     stream = vp(torch.cuda.current_stream().cuda_stream)
     assert L.fls_set_workspace(vp(ws.data_ptr()), ws.numel(), stream) == 0
     calls = [vp(b.data_ptr()) for b in blobs]

@@ -86,3 +86,14 @@ def test_inspect_validates_headers(fls, oracle_mod):
         with pytest.raises(fls.FlsError) as e:
             fls.fls_inspect(bad.tobytes())
         assert e.value.code == fls.EFORMAT
+
+
+def test_measurement_probe_library_loads(fls):
+    """libfls_probe.so (the plain streaming read bench.py uses as its empirical ceiling) is built beside the
+    library, exports its one entry point and rejects bad arguments before any launch."""
+    from paper_2309_10285_amd import stream_probe
+
+    L = stream_probe.lib()
+    assert L.fls_probe_stream_read(None, 1024, 8, 8, 16, None) == -1
+    assert L.fls_probe_stream_read(16, 1024, 8, 5, 16, None) == -1   # unroll not offered
+    assert L.fls_probe_stream_read(16, 1024, 0, 8, 16, None) == -1   # empty grid

@@ -52,6 +52,9 @@ def test_bench_line_carries_the_contract_fields():
     roof = out["roofline"]
     assert roof["bound"] == "hbm" and roof["peak"] == 8000.0 and roof["unit"] == "GB/s"
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-3
+    assert roof["traffic"] is None  # nobody measured C1's HBM traffic: the line must not pretend
+    ceil = out["stream_ceiling"]
+    assert ceil["GBps"] > 0 and ceil["bytes"] == out["config"]["blob_bytes"]
     cpu = out["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"]
-    assert out["parity"]["max_rel_err_vs_oracle"] <= out["parity"]["tolerance"]
+    assert out["parity"]["max_rel_err_vs_oracle"] <= out["parity"]["tolerance"] and out["parity"]["rows_checked"] == 1024

@@ -259,38 +259,6 @@ def test_spmm_wide_n_split_bands(fls, oracle_mod):
         assert _rel_err(C, oracle_mod.ref_spmm_f64(W, X)) <= TOL
 
 
-def test_full_size_c2_sampled_rows_and_blob(fls, oracle_mod):
-    """The benchmark configuration itself (W 28672 x 7168, 80 % magnitude-pruned, N = 16), as bench.py launches it:
-    the whole blob against the oracle's, and C on sampled row bands (first, two inner, last) that the oracle
-    computes row by row."""
-    cfg = wl.CONFIGS["C2"]
-    W, X = wl.make_inputs(cfg)
-    blob, st, C = _run_spmm(fls, W, X, cfg.N)
-    ref_blob = oracle_mod.ref_compress(W)
-    assert st["bytes_total"] == ref_blob.size
-    assert np.array_equal(blob.cpu().numpy(), ref_blob)
-    for band in (0, 77, 150, cfg.M // 128 - 1):
-        m0, m1 = band * 128, band * 128 + 128
-        ref = oracle_mod.ref_spmm_f64(W, X, rows=(m0, m1))[:, m0:m1]
-        assert _rel_err(C[:, m0:m1], ref) <= TOL
-
-
-@pytest.mark.parametrize("name", ["C3", "C4"])
-def test_full_size_other_configs_sampled_rows(fls, oracle_mod, name):
-    """C3 (N = 32, two column blocks per wave) and C4 (N = 64: the 64-column pass with K slices and the second,
-    adding kernel) at their full sizes: the blob's size and header against the oracle's count, C on sampled row
-    bands (first, inner, last) that the oracle computes row by row."""
-    cfg = wl.CONFIGS[name]
-    W, X = wl.make_inputs(cfg)
-    blob, st, C = _run_spmm(fls, W, X, cfg.N)
-    assert st["nnz"] == int(np.count_nonzero(W))
-    bands = cfg.M // 128
-    for band in (0, bands // 3, bands - 1):
-        m0, m1 = band * 128, band * 128 + 128
-        ref = oracle_mod.ref_spmm_f64(W, X, rows=(m0, m1))[:, m0:m1]
-        assert _rel_err(C[:, m0:m1], ref) <= TOL
-
-
 def test_back_to_back_shapes_share_one_workspace(fls, oracle_mod):
     """Calls of different shapes and widths, alternating, on one registered workspace: flags raised by a launch are lowered by it,
     nothing is cleared in between, and the kernels' error word (a hand-over wait that gave up) stays 0."""
@@ -438,7 +406,7 @@ def test_piece_boundary_at_the_edge_of_the_offset_window(fls, oracle_mod):
     window of TileOffsets: the load side looks past the end of the piece and moves the window on, and the next
     piece starts one tile before the new window.  With 256 CUs that takes at least 129 000 tiles; this shape
     (258 bands x 500 K tiles) has four such waves, in bands 65, 81, 194 and 210 (a first version read the wrong
-    offset there).  C is checked on those bands and their neighbours against the oracle."""
+    offset there).  The whole of C is checked against the oracle."""
     import torch
 
     M, K, N = 258 * 128, 500 * 32, 16
@@ -453,10 +421,10 @@ def test_piece_boundary_at_the_edge_of_the_offset_window(fls, oracle_mod):
     torch.cuda.synchronize()
     C = C.cpu().numpy()
     assert not np.isnan(C).any()
-    for band in (0, 64, 65, 66, 81, 194, 210, 257):
-        m0, m1 = band * 128, band * 128 + 128
-        ref = oracle_mod.ref_spmm_f64(W[m0:m1], X)
-        assert _rel_err(C[:, m0:m1], ref) <= TOL, band
+    ref = oracle_mod.ref_spmm_f64(W, X)
+    scale = float(np.abs(ref).max())
+    per_band = np.abs(C.astype(np.float64) - ref).reshape(N, M // 128, 128).max(axis=(0, 2)) / scale
+    assert per_band.max() <= TOL, ("worst band", int(per_band.argmax()))
     fls.fls_forget(blob)
 
 
@@ -464,7 +432,7 @@ def test_split_bands_after_wide_passes_many_repeats(fls, oracle_mod):
     """N = 222 on a matrix whose bands are cut between workgroups: three 64-column passes, then a 32-column pass
     whose partial-sum slots lie where the wide passes' partial results were a moment ago.  A hand-over that raised
     its flag before its partial sum had left the XCD's L2 gave a wrong band about once in a thousand such calls;
-    the first result is checked against the oracle on sampled bands, then 3000 more calls must repeat it to within
+    the first result is checked against the oracle in full, then 3000 more calls must repeat it to within
     fp16 rounding (inside a workgroup the waves' sums are added in the order they finish, so the last bit may
     differ; a wrong band is off by tens of percent)."""
     import torch
@@ -479,9 +447,10 @@ def test_split_bands_after_wide_passes_many_repeats(fls, oracle_mod):
     fls.fls_spmm(blob, Xd, first, M, K, N)
     torch.cuda.synchronize()
     got = first.cpu().numpy()
-    for band in (0, 77, M // 128 - 1):
-        m0, m1 = band * 128, band * 128 + 128
-        assert _rel_err(got[:, m0:m1], oracle_mod.ref_spmm_f64(W[m0:m1], X)) <= TOL
+    assert not np.isnan(got).any()
+    ref = oracle_mod.ref_spmm_f64(W, X)  # the whole of C: every later call is compared with this first result
+    assert float(np.abs(got.astype(np.float64) - ref).max()) / float(np.abs(ref).max()) <= TOL
+    del ref
     C = torch.empty_like(first)
     ref32 = first.float()
     scale = float(ref32.abs().max())
