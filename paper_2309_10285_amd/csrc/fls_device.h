@@ -6,19 +6,6 @@
 
 namespace fls {
 
-// Debug builds only (-DFLS_TRACE): 100 MHz timestamps of the hand-over steps, kept in the unused
-// tail of the flag area: flags[65536 + 16 * workgroup + k].
-#ifdef FLS_TRACE
-#define FLS_STAMP(cnt, wg, k)                                                             \
-  do {                                                                                    \
-    if ((threadIdx.x & 63) == 0) (cnt)[65536 + 16 * (wg) + (k)] = (uint32_t)wall_clock64(); \
-  } while (0)
-#else
-#define FLS_STAMP(cnt, wg, k) \
-  do {                        \
-  } while (0)
-#endif
-
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float float4v __attribute__((ext_vector_type(4)));
@@ -102,15 +89,15 @@ struct WgReduceLds {
   static constexpr uint32_t kSlots = 2;
   static constexpr int kParts = 4;  // a slot is added to in four parts, each under its own lock
   float4v slot[kSlots][NB * kRowBlocks * 64];
-  uint32_t cnt[2];           // tiles added to the slot so far
-  uint32_t gen[2];           // how many bands the slot has served
-  uint32_t lock[2][kParts];  // 1 while a wave is adding to that part of the slot
+  uint32_t cnt[kSlots];           // tiles added to the slot so far
+  uint32_t gen[kSlots];           // how many bands the slot has served
+  uint32_t lock[kSlots][kParts];  // 1 while a wave is adding to that part of the slot
 };
 
 template <int NB>
 __device__ __forceinline__ void wg_reduce_init(WgReduceLds<NB>* red, int tid, int nthreads) {
   for (int i = tid; i < (int)WgReduceLds<NB>::kSlots * NB * kRowBlocks * 64; i += nthreads) (&red->slot[0][0])[i] = float4v{0.f, 0.f, 0.f, 0.f};
-  if (tid < 2) {
+  if (tid < (int)WgReduceLds<NB>::kSlots) {
     red->cnt[tid] = 0;
     red->gen[tid] = 0;
 #pragma unroll
@@ -258,7 +245,6 @@ __device__ __forceinline__ void owner_finish(const OutParams& o, float4v (&acc)[
     // workgroup q raises its flag once per launch and nobody else looks at it: down again for the next launch
     if (seen && lane == 0) __hip_atomic_store(o.flags + q, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  FLS_STAMP(o.flags, wg, 6);
   // the acquire that pairs with the contributors' release: nothing this XCD's caches still hold of
   // the slots may serve the loads below
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
@@ -360,14 +346,10 @@ template <int NB>
 __device__ __forceinline__ void hand_over_finish(const OutParams& o, float4v (&acc)[kRowBlocks][NB],
                                                  const HandoverState& st, uint32_t wg, uint32_t P, int lane) {
   if (st.publish) {
-    FLS_STAMP(o.flags, wg, 3);
     publish_partial(o, wg, lane, st.released);
-    FLS_STAMP(o.flags, wg, 4);
   }
   if (st.own) {
-    FLS_STAMP(o.flags, wg, 5);
     owner_finish<NB>(o, acc, st.own_band, wg, P, lane);
-    FLS_STAMP(o.flags, wg, 7);
   }
 }
 

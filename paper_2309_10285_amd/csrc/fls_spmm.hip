@@ -61,7 +61,6 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   WgReduceLds<NB>* red = (WgReduceLds<NB>*)(lds + WAVES * kWaveLds);
   wg_reduce_init<NB>(red, threadIdx.x, WAVES * 64);
   __syncthreads();  // the only barrier: from here on the waves run independently
-  if (wave == 0) FLS_STAMP(p.out.flags, blockIdx.x, 0);
   if (t0 >= t1) return;
 
   unsigned char* tile = lds + wave * kWaveLds;
@@ -202,7 +201,6 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   // Hand-over of the piece of `tiles` tiles that just ended in `band`.
   HandoverState hs;
   auto hand_over = [&](uint32_t band, uint32_t tiles) {
-    if (tc == t1) FLS_STAMP(p.out.flags, 256 + blockIdx.x, wave);  // debug builds: end of every wave's run
     if (FLS_ABLATE & 1) {
       float sum = 0.f;  // keeps every accumulator alive
 #pragma unroll
@@ -255,7 +253,6 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
       issue(ss, sx, b, e);
       compute();
     }
-    if (tc == t0) FLS_STAMP(p.out.flags, 512 + blockIdx.x, wave);  // debug builds: the wave's first tile is done
     ++tc;
   };
 
@@ -268,7 +265,6 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   // band's owner, or stores it as the workgroup's partial sum.
   const bool one_band = NB == 1 && share0 / KT == (share1 - 1) / KT && share1 - share0 >= (uint32_t)WAVES;
   auto one_band_sum = [&](uint32_t band) {
-    if (tc == t1) FLS_STAMP(p.out.flags, 256 + blockIdx.x, wave);
 #pragma unroll
     for (int rb = 0; rb < kRowBlocks; ++rb) *(float4v*)(tile + rb * 1024 + lane * 16) = acc[rb][0];
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -320,7 +316,6 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     }
   }
   hand_over_finish<NB>(p.out, acc, hs, blockIdx.x, gridDim.x, lane);
-  if (wave == 0) FLS_STAMP(p.out.flags, blockIdx.x, 2);
 }
 
 // ---------------------------------------------------------------- host launcher
