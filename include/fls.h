@@ -47,8 +47,9 @@ enum {
   FLS_EFORMAT = -4,    /* blob header: bad magic / version / geometry, or M, K differ from the call */
   FLS_EWORKSPACE = -5, /* no workspace registered, or it is too small for this call */
   FLS_EHIP = -6,       /* a HIP call failed (the HIP error stays readable with hipGetLastError) */
-  FLS_EHANDOVER = -7   /* a kernel gave up waiting for another workgroup's partial sum: results of the calls
+  FLS_EHANDOVER = -7,  /* a kernel gave up waiting for another workgroup's partial sum: results of the calls
                           since the last check are not to be trusted (fls_check_workspace) */
+  FLS_ESCRATCH = -8    /* fls_spmm_noalloc: the call needs more scratch than the library's static array holds */
 };
 
 /* opaque stream handle: pass a hipStream_t (NULL = the default stream) */
@@ -152,6 +153,31 @@ int fls_check_workspace(fls_stream_t stream);
  */
 int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int64_t K, int64_t N,
              fls_stream_t stream);
+
+/*
+ * fls_spmm for callers that cannot allocate device memory or wait on a stream: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and results as
+ * fls_spmm, but
+ *   - the split-K scratch (hand-over flags, error word, fp32 partial sums) is a static device array
+ *     inside the library, FLS_NOALLOC_SCRATCH_BYTES large, present on every GPU the library runs on
+ *     from load time to the end of the process: no workspace has to be registered, and none is used;
+ *   - the blob's statistics come from the caller (stats_host: as filled by fls_compress or
+ *     fls_inspect for this blob; read during the call only) instead of a header read-back, so the
+ *     call copies nothing, waits for nothing and keeps no state about the blob.
+ * It calls no hipMalloc, hipFree or allocating library routine.  Limit: N <= FLS_NOALLOC_MAX_N (wider
+ * calls need repacked X and larger partial sums than the array holds): FLS_ESCRATCH beyond it.
+ * stats_host must describe the blob at Wc_dev (same M, K, tile geometry): FLS_EFORMAT otherwise; a
+ * max_tile_words smaller than the blob's costs speed only, as with fls_spmm.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams,
+ * two threads) race, and must be serialised by the caller.  Each call clears the array's control
+ * words first (a small kernel on `stream`).  fls_check_workspace also reports a hand-over that
+ * gave up inside this call.
+ * Errors: FLS_EINVAL, FLS_EALIGN, FLS_EFORMAT, FLS_ESCRATCH, FLS_EHIP.
+ */
+#define FLS_NOALLOC_MAX_N 32
+#define FLS_NOALLOC_SCRATCH_BYTES (8192u + 512u * 2u * 2048u * 4u)
+int fls_spmm_noalloc(const void* Wc_dev, const fls_stats* stats_host, const void* X_dev, void* C_dev, int64_t M,
+                     int64_t K, int64_t N, fls_stream_t stream);
 
 /* Drops what fls_spmm remembers about a blob address (NULL: about all of them). */
 void fls_forget(const void* Wc_dev);

@@ -26,6 +26,36 @@ void* g_ws = nullptr;
 size_t g_ws_bytes = 0;
 int g_num_cus = 0;
 
+// Scratch of fls_spmm_noalloc: the same areas a registered workspace has (control words, then the
+// fp32 partial sums of up to 32 columns), in device memory that exists from the moment the library
+// is loaded.  Host code never uses the array's name as an address: hipGetSymbolAddress gives the
+// address on the current device (every device has its own copy), looked up once per device.
+constexpr size_t kScratchControlBytes = 8192;  // 512 flags, the error word, spare
+constexpr size_t kScratchPartsBytes = (size_t)fls::kMaxWorkgroups * 2 * 2048 * sizeof(float);  // 8 MiB
+constexpr size_t kScratchBytes = kScratchControlBytes + kScratchPartsBytes;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};  // by device id; guarded by g_mu
+
+// Address of `scratch` on the current device (nullptr after setting *err on failure).
+unsigned char* scratch_on_current_device(int* err) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    *err = FLS_EHIP;
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      *err = FLS_EHIP;
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = (unsigned char*)ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline uint64_t round_up(uint64_t v, uint64_t m) { return (v + m - 1) / m * m; }
@@ -191,13 +221,26 @@ int fls_set_workspace(void* ws_dev, size_t bytes, fls_stream_t stream) {
 
 int fls_check_workspace(fls_stream_t stream) {
   void* ws;
+  unsigned char* st = nullptr;
   {
     std::lock_guard<std::mutex> lk(g_mu);
-    if (!g_ws || g_ws_bytes < kCounterAreaBytes) return FLS_EWORKSPACE;
-    ws = g_ws;
+    int dev = 0;
+    if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) st = g_scratch_ptr[dev];
+    if (!st && (!g_ws || g_ws_bytes < kCounterAreaBytes)) return FLS_EWORKSPACE;
+    ws = g_ws && g_ws_bytes >= kCounterAreaBytes ? g_ws : nullptr;
   }
   hipStream_t s = (hipStream_t)stream;
   uint32_t word = 0;
+  if (st) {  // the scratch of fls_spmm_noalloc, if this device has used it
+    if (hipMemcpyAsync(&word, (const uint32_t*)st + fls::kMaxWorkgroups, sizeof(word), hipMemcpyDeviceToHost, s) != hipSuccess)
+      return FLS_EHIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return FLS_EHIP;
+    if (word != 0) {
+      if (fls::launch_fill_zero(st, kScratchControlBytes, s) != hipSuccess) return FLS_EHIP;
+      return FLS_EHANDOVER;
+    }
+    if (!ws) return FLS_OK;
+  }
   if (hipMemcpyAsync(&word, (const uint32_t*)ws + fls::kMaxWorkgroups, sizeof(word), hipMemcpyDeviceToHost, s) != hipSuccess)
     return FLS_EHIP;
   if (hipStreamSynchronize(s) != hipSuccess) return FLS_EHIP;
@@ -263,6 +306,41 @@ int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int6
   return fls::launch_spmm(a, (hipStream_t)stream) == hipSuccess ? FLS_OK : FLS_EHIP;
 }
 
+int fls_spmm_noalloc(const void* Wc_dev, const fls_stats* stats_host, const void* X_dev, void* C_dev, int64_t M,
+                     int64_t K, int64_t N, fls_stream_t stream) {
+  if (!stats_host) return FLS_EINVAL;
+  int rc = check_mm_args(Wc_dev, X_dev, C_dev, M, K, N);
+  if (rc != FLS_OK) return rc;
+  if (N > FLS_NOALLOC_MAX_N) return FLS_ESCRATCH;  // partial sums of wider calls do not fit the static array
+  // the caller's stats stand in for the header read-back of fls_spmm: nothing is copied, nothing is waited for
+  if (stats_host->format_version != FLS_FORMAT_VERSION || stats_host->tile_m != FLS_TILE_M || stats_host->tile_k != FLS_TILE_K ||
+      stats_host->M != (uint64_t)M || stats_host->K != (uint64_t)K || stats_host->num_tiles != num_tiles(M, K) ||
+      stats_host->max_tile_words > FLS_TILE_M * FLS_TILE_K || stats_host->bytes_offsets != 4 * n_off_of(num_tiles(M, K)))
+    return FLS_EFORMAT;
+  unsigned char* ptr = scratch_on_current_device(&rc);
+  if (!ptr) return rc;
+  const int cus = num_cus();
+  if (cus <= 0) return FLS_EHIP;
+  hipStream_t s = (hipStream_t)stream;
+  // the array keeps what the last call left: flags and error word start every call at zero (a fill
+  // kernel, not a memset node, so that the call can be recorded into a graph)
+  if (fls::launch_fill_zero(ptr, kScratchControlBytes, s) != hipSuccess) return FLS_EHIP;
+  fls::SpmmLaunch a;
+  a.offs = (const uint32_t*)((const unsigned char*)Wc_dev + FLS_HEADER_BYTES);
+  a.words = a.offs + n_off_of(num_tiles(M, K));
+  a.X = (const _Float16*)X_dev;
+  a.C = (_Float16*)C_dev;
+  a.flags = (uint32_t*)ptr;
+  a.parts = (float*)(ptr + kScratchControlBytes);
+  a.xpack = nullptr;  // only calls of more than 32 columns repack X
+  a.M = (uint32_t)M;
+  a.K = (uint32_t)K;
+  a.N = (uint32_t)N;
+  a.max_tile_words = (uint32_t)stats_host->max_tile_words;
+  a.num_cus = cus;
+  return fls::launch_spmm(a, s) == hipSuccess ? FLS_OK : FLS_EHIP;
+}
+
 int fls_dense_gemm(const void* W_dev, const void* X_dev, void* C_dev, int64_t M, int64_t K, int64_t N,
                    fls_stream_t stream) {
   int rc = check_mm_args(W_dev, X_dev, C_dev, M, K, N);
@@ -300,6 +378,7 @@ const char* fls_strerror(int code) {
     case FLS_EFORMAT: return "compressed blob header is malformed or does not match M, K";
     case FLS_EWORKSPACE: return "workspace missing or too small (see fls_workspace_bytes / fls_set_workspace)";
     case FLS_EHIP: return "a HIP runtime call failed";
+    case FLS_ESCRATCH: return "the call needs more scratch than the library's static array holds (fls_spmm_noalloc: N <= 32)";
     case FLS_EHANDOVER: return "a kernel gave up waiting for another workgroup's partial sum; results since the last check are not to be trusted";
     default: return "unknown error code";
   }
