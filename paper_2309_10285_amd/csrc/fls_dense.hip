@@ -270,6 +270,7 @@ static hipError_t launch_dense_wide(const DenseLaunch& a, uint32_t n0, hipStream
   p.offs = nullptr;
   p.words = nullptr;
   p.W = a.W;
+  p.X = nullptr;
   p.Xp = a.xpack;
   p.C = a.C;
   p.parts = a.parts;
@@ -283,7 +284,7 @@ static hipError_t launch_dense_wide(const DenseLaunch& a, uint32_t n0, hipStream
   const uint32_t groups = (p.bands + 3u) / 4u;
   hipLaunchKernelGGL((dense_wide_kernel<FLS_DENSE_WIDE_NS>), dim3(groups * p.S), dim3(256), 0, stream, p);
   hipError_t e = hipGetLastError();
-  if (e == hipSuccess && p.S > 1) e = launch_wide_reduce(p, stream);
+  if (e == hipSuccess && p.S > 1) e = launch_wide_reduce(p, false, stream);
   return e;
 }
 

@@ -55,14 +55,14 @@ inline uint32_t wide_slices(uint32_t bands, uint32_t KT, int cus) {
   const uint32_t by_length = KT / 16u > 0 ? KT / 16u : 1u;
   return S < by_length ? S : by_length;
 }
-// The sparse 64-column pass: a workgroup takes two bands and a K slice, two waves per band (one
-// per half of the slice), and writes one partial result per band and slice.  Slices per pair of
-// bands: as many as fill the CUs, none shorter than 32 tiles (16 per wave).
-inline uint32_t wide_pair_slices(uint32_t bands, uint32_t KT, int cus) {
+// The sparse 64-column pass: a workgroup takes four bands (one per wave) and a K slice made of whole
+// loop bodies of `body` tiles, and writes one partial result per band and slice.  Slices per group
+// of four bands: as many as fill the CUs, none shorter than two bodies.
+inline uint32_t wide_quad_slices(uint32_t bands, uint32_t KT, int cus, uint32_t body) {
   if (cus > (int)kMaxWorkgroups) cus = (int)kMaxWorkgroups;
-  const uint32_t pairs = (bands + 1) / 2;
-  uint32_t S = pairs < (uint32_t)cus ? (uint32_t)cus / pairs : 1u;
-  const uint32_t by_length = KT / 32u > 0 ? KT / 32u : 1u;
+  const uint32_t quads = (bands + 3) / 4;
+  uint32_t S = quads < (uint32_t)cus ? (uint32_t)cus / quads : 1u;
+  const uint32_t by_length = KT / (2u * body) > 0 ? KT / (2u * body) : 1u;
   return S < by_length ? S : by_length;
 }
 // fp32 values of the split-K partial sums: [workgroup][column blocks][128 x 16] for the passes of
@@ -110,7 +110,8 @@ struct WideParams {
   const uint32_t* offs;   // TileOffsets (sparse pass)
   const uint32_t* words;  // NonZeros (sparse pass)
   const _Float16* W;      // dense matrix (dense pass)
-  const _Float16* Xp;     // X in fragment order: [K tile][column block of all N][lane][8 halves]
+  const _Float16* X;      // X as the caller lays it out, column-major K x N (sparse pass)
+  const _Float16* Xp;     // X in fragment order: [K tile][column block of all N][lane][8 halves] (dense pass)
   _Float16* C;
   float* parts;           // [band][slice][column block][row block][lane] float4, used when S > 1
   uint32_t M, K, N, n0, KT, bands, S;
@@ -120,8 +121,9 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream);
 // X -> xpack (fragment order, all N columns), then one 64-column pass per call of launch_spmm_wide from column n0 on
 hipError_t launch_xpack(const _Float16* X, _Float16* xpack, uint32_t K, uint32_t N, hipStream_t stream);
 hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, hipStream_t stream);
-// C = sum over the S slices of parts, in slice order (the second kernel of a 64-column pass with S > 1)
-hipError_t launch_wide_reduce(const WideParams& p, hipStream_t stream);
+// C = sum over the S slices of parts, in slice order (the second kernel of a 64-column pass with S > 1);
+// layout32: the partial results are in the 32x32 accumulator layout (sparse pass), else 16x16 (dense pass)
+hipError_t launch_wide_reduce(const WideParams& p, bool layout32, hipStream_t stream);
 hipError_t launch_dense(const DenseLaunch& a, hipStream_t stream);
 // phase 1: per-tile counts, prefix sums, header (everything but the words)
 hipError_t launch_compress_index(const CompressLaunch& a, hipStream_t stream);

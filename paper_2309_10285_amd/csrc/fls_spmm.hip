@@ -384,10 +384,6 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
   // rounds of 256 no longer fit its registers): a matrix with denser tiles - less than 40 % sparse
   // somewhere - takes 32-column passes throughout.
   const bool wide_ok = a.max_tile_words <= 10 * 256;
-  if (a.N > kGroupCols && wide_ok) {
-    hipError_t e = launch_xpack(a.X, a.xpack, a.K, a.N, stream);  // the 64-column passes read X from a copy in fragment order
-    if (e != hipSuccess) return e;
-  }
   for (uint32_t n0 = 0; n0 < a.N;) {
     p.out.n0 = n0;
     const uint32_t left = a.N - n0;

@@ -2,48 +2,49 @@
 // sizes, re-cut for gfx950).
 //
 // A workgroup has four waves, one per SIMD with the whole register file (128 accumulator
-// registers, a deep ring of tiles in flight), each with a tile run of its own; in the tile loop
-// the waves share nothing but the CU: no barrier, no waiting.  With 64 columns a tile needs 4 KB of X against some
-// 1.6 - 5 KB of compressed W, so how X reaches the MFMAs matters as much as W: a first kernel
-// repacks X once per call into MFMA fragment order, after which a wave's four B fragments of a K
-// tile are four fully coalesced 1 KB loads from L2, kept a few tiles ahead in a register ring of
-// their own.  (Fragments loaded from X as the caller lays it out touch sixteen cache lines per
-// load and bound the kernel; X shared between the four waves through LDS - double-buffered
-// chunks, one barrier per four tiles - costs LDS bandwidth and lockstep, and measured 6 - 10 %
-// slower for sparse tiles.)
+// registers, a deep ring of tiles in flight), and takes four row bands (one per wave) x one K slice:
+// the four waves walk the same K tiles side by side, so the X rows of a tile are fetched once per
+// workgroup - straight from the caller's X into LDS, a loop body (4 or 8 tiles) ahead, by all four
+// waves together - and every wave reads its B fragments from there.  With 64 columns a tile needs
+// 4 KB of X against some 1.6 - 5 KB of compressed W, and fragments fetched from L2 by every wave
+// for itself cost more vector-memory time than the stream of words.  The waves meet at one barrier
+// per loop body (after storing their part of the next X chunk, before reading from it); everything
+// else of the tile loop is private to a wave.
 //
-// Work is cut as (pair of bands) x (K slice), S slices per pair so that the grid fills the CUs;
-// inside a workgroup each band has two waves, one per half of the slice, whose accumulators meet
-// in LDS when both are done (the one barrier of the kernel).  The sum is the band's partial
-// result for the slice: with S = 1 it is stored to C directly, otherwise to a partial-sum area
-// [band][slice] that a second, small kernel adds up in slice order and converts (no flags, no
-// waiting between workgroups).  Two waves per band halve the partial sums that go through memory
-// against one wave per band and slice.
+// Work is cut as (group of four bands) x (K slice), S slices per group so that the grid fills the
+// CUs.  With S = 1 a wave's sum is its band's result and goes to C directly, otherwise to a
+// partial-sum area [band][slice] that a second, small kernel adds up in slice order and converts
+// (no flags, no waiting between workgroups, deterministic).
 //
 // Inside a wave the stages are those of the narrow kernel - register ring of tiles, extraction by
-// 2 B LDS stores, 16 B fragment reads, v_mfma_f32_16x16x32_f16 - software-pipelined, since no
-// second wave shares the SIMD: a step reads the fragments of its tile, extracts the next tile
-// behind those reads, and runs its MFMAs spread between the extraction's instructions.
+// 2 B LDS stores, 16 B fragment reads - software-pipelined by hand, since no second wave shares the
+// SIMD: the MFMAs of a tile are asm statements in a fixed order with the step's other work (re-zero
+// the tile, extract the next one, read its fragments, refill the ring, X chunk traffic) dealt out
+// between them, and they work on fragments that were read during the step before.  The shape is
+// v_mfma_f32_32x32x16_f16 (16 per tile).
+#include <type_traits>
+
 #include "fls_device.h"
 #include "fls_launch.h"
 
 // Latency-breakdown builds (see fls_spmm.hip): 2 no MFMA, 4 no extract, 8 no re-zeroing, 16 no LDS
-// fragment reads, 32 no global loads of the words, 256 no loads of X.  0 in the library.
+// fragment reads, 32 no global loads of the words, 256 no X traffic (loads, LDS stores, B fragment
+// reads).  0 in the library.
 #ifndef FLS_ABLATE
 #define FLS_ABLATE 0
 #endif
 
 namespace fls {
 
-constexpr int kWideWaves = 4;                   // two bands x two halves of the K slice
-constexpr int kWideNB = 4;                      // column blocks per pass
+constexpr int kWideWaves = 4;                   // four bands, one wave each
+constexpr int kWideNB = 4;                      // 16-column blocks per pass
 constexpr int kWideTileLds = kTileBytes + 16;   // a wave's tile + the slot padding words land in
-constexpr int kWideLdsBytes = kWideWaves * kWideTileLds + 2 * kWideNB * kRowBlocks * 64 * 16;  // tiles + two bands' accumulators
 
-// X in MFMA fragment order: block (K tile kt, column block nb) holds, for lane l = 16 g + c, the 8
-// halves X[32 kt + 8 g .. +7][16 nb + c] (zeros for columns past N).  One wave per pair of K tiles
-// and column block, so that it uses the whole 128 B line of each of its 16 columns; loads are
-// quad-contiguous (lane j reads column j >> 2, chunk j & 3), stores go to the fragment position.
+// X in MFMA fragment order, for the dense 64-column pass: block (K tile kt, column block nb) holds,
+// for lane l = 16 g + c, the 8 halves X[32 kt + 8 g .. +7][16 nb + c] (zeros for columns past N).
+// One wave per pair of K tiles and column block, so that it uses the whole 128 B line of each of
+// its 16 columns; loads are quad-contiguous (lane j reads column j >> 2, chunk j & 3), stores go to
+// the fragment position.
 __global__ __launch_bounds__(256) void xpack_kernel(const _Float16* X, _Float16* Xp, uint32_t K, uint32_t N, uint32_t units,
                                                     uint32_t blocks) {
   const uint32_t u = blockIdx.x * 4 + (threadIdx.x >> 6);  // (pair of K tiles, column block)
@@ -64,77 +65,181 @@ __global__ __launch_bounds__(256) void xpack_kernel(const _Float16* X, _Float16*
   }
 }
 
-template <int R, int NS, int XS>
+// Compile-time loop: f(integral_constant<int, I>) for I in [B, E).
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(std::integral_constant<int, B>{});
+    static_for<B + 1, E>(f);
+  }
+}
+
+// acc += a . b with the accumulator kept where it is (sixteen AGPRs): as an asm statement, so that
+// the instruction keeps its place between the memory operations around it.
+//
+// The 64-column pass multiplies with v_mfma_f32_32x32x16_f16 rather than 16x16x32: half as many
+// instructions for the same work, each leaving eight issue slots in its shadow.  Operand layouts
+// of the 32x32x16 shape, lane l = 32 h + c:
+//   A: row c of the 32-row block, the 8 k of chunk h of the 16-k step;  B: column c, the same 8 k;
+//   C/D: column c, rows 8 q + 4 h + (0..3) in registers 4 q .. 4 q + 3, q = 0..3.
+typedef float float16v __attribute__((ext_vector_type(16)));
+__device__ __forceinline__ void mfma_in_place(float16v& acc, const half8& a, const half8& b) {
+  asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+constexpr int kRowBlocks32 = kTileM / 32;  // 32-row blocks of a tile
+constexpr int kColBlocks32 = 2;            // 32-column blocks of a pass
+constexpr int kSteps16 = kTileK / 16;      // 16-k steps of a tile
+
+// Converts a wave's 128 x 64 accumulators (32x32 layout) to fp16 and stores them to column-major C.
+__device__ __forceinline__ void store_band32(_Float16* C, uint32_t M, uint32_t N, uint32_t n0,
+                                             const float16v (&acc)[kRowBlocks32][kColBlocks32], uint32_t band, int lane) {
+  const uint32_t c = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int cb = 0; cb < kColBlocks32; ++cb) {
+    const uint32_t n = n0 + cb * 32 + c;
+    if (n < N) {
+#pragma unroll
+      for (int rb = 0; rb < kRowBlocks32; ++rb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          half4 v;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) v[r] = (_Float16)acc[rb][cb][4 * q + r];
+          *(half4*)(C + (size_t)n * M + band * kTileM + rb * 32 + q * 8 + h * 4) = v;
+        }
+    }
+  }
+}
+
+// LDS of a workgroup: two X chunks (a chunk = the NS K tiles of a loop body x 64 columns, 4 KB per
+// tile), then the four waves' tiles.  The chunks come first so that the two lie 2^k apart and a
+// body switches between them by flipping one address bit.
+template <int NS>
+constexpr int wide_lds_bytes() { return 2 * NS * 4096 + kWideWaves * kWideTileLds; }
+
+template <int R, int NS>
 __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p) {
   constexpr int NB = kWideNB;
-  static_assert(NS % XS == 0, "the unrolled ring must hold whole turns of the X ring");
+  static_assert(NS == 4 || NS == 8, "a body is 4 or 8 tiles");
+  constexpr uint32_t kChunkBytes = NS * 4096u;
   extern __shared__ __align__(16) unsigned char lds[];
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  // the workgroup: two row bands x the two halves of its K slice
-  const uint32_t pair = blockIdx.x / p.S, slice = blockIdx.x - pair * p.S;
-  const uint32_t band = pair * 2 + (wave & 1u), half = wave >> 1;
-  const bool active = band < p.bands;  // a wave past the last band walks an empty run and meets the barrier
+  // the workgroup: four row bands (one per wave) x one K slice, which all four waves walk together
+  const uint32_t quad = blockIdx.x / p.S, slice = blockIdx.x - quad * p.S;
+  const uint32_t band = quad * 4 + wave;
+  const bool active = band < p.bands;  // a wave past the last band loads no words but shares the X work
   const uint32_t KT = p.KT, T = p.bands * KT;
-  const uint32_t ka = (uint32_t)((uint64_t)slice * KT / p.S), kb = (uint32_t)((uint64_t)(slice + 1) * KT / p.S);
-  const uint32_t km = ka + (kb - ka + 1) / 2;
-  const uint32_t k0 = half ? km : ka, k1 = active ? (half ? kb : km) : k0;
-  const uint32_t t0 = active ? band * KT + k0 : T, t1 = active ? band * KT + k1 : T;
-  const uint32_t bodies = (k1 - k0 + NS - 1) / NS;  // of NS steps each
+  // the slice: whole bodies of NS tiles, cut evenly; the K tiles that fill no body go to the last slice
+  const uint32_t bodies_all = KT / NS;
+  const uint32_t b0 = (uint32_t)((uint64_t)slice * bodies_all / p.S), b1 = (uint32_t)((uint64_t)(slice + 1) * bodies_all / p.S);
+  const uint32_t bodies = b1 - b0;
+  const uint32_t k0 = b0 * NS, k1 = k0 + bodies * NS;          // tiles of the pipelined loop
+  const uint32_t ktail = slice + 1 == p.S ? KT : k1;           // ... and of the plain loop behind it
+  const uint32_t t0 = active ? band * KT + k0 : T;
+  const uint32_t ntiles = active ? bodies * NS : 0;            // tiles this wave loads words for
 
-  unsigned char* tile = lds + wave * kWideTileLds;
+  unsigned char* tile = lds + 2 * kChunkBytes + wave * kWideTileLds;
   const u32x4 zero4 = {0u, 0u, 0u, 0u};
 #pragma unroll
   for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
 
-  float4v acc[kRowBlocks][NB];
+  float16v acc[kRowBlocks32][kColBlocks32];
 #pragma unroll
-  for (int rb = 0; rb < kRowBlocks; ++rb)
+  for (int rb = 0; rb < kRowBlocks32; ++rb)
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) acc[rb][nb] = float4v{0.f, 0.f, 0.f, 0.f};
+    for (int cb = 0; cb < kColBlocks32; ++cb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[rb][cb][r] = 0.f;
 
-  // X: tile kt holds blocks of all columns of the call; this pass takes four from block n0 / 16 on.
-  const uint32_t xblocks = (p.N + 15u) / 16u;
-  const __amdgpu_buffer_rsrc_t xrsrc =
-      __builtin_amdgcn_make_buffer_rsrc((void*)p.Xp, 0, (int)(KT * xblocks * 1024u), kBufferFlags);
-  const uint32_t xlane = (p.n0 / 16u) * 1024u + (uint32_t)lane * 16u;
-  // the last pass of a call may have fewer than four column blocks left: the others read as zero
-  const uint32_t xvalid = xblocks - p.n0 / 16u;
-  // One tile's four blocks into a stage of the X ring.  Tiles past the slice (the padding of the
-  // last body) must contribute nothing even if X holds Inf or NaN further along K: their X reads
-  // as zero.  (Everything that may leave the buffer is in the per-lane offset: that is the part
-  // the bounds check of a raw buffer looks at.)
-  uint32_t xti = k0;
-  auto xissue = [&](u32x4(&xq)[NB]) {
-    const uint32_t base = xti * xblocks * 1024u + xlane;
+  // ---- X, from the caller's layout into LDS, once per workgroup and K tile.
+  // A load instruction takes 8 columns x 64 k (two K tiles): lane l reads the 16 B of column
+  // l >> 3, k chunk l & 7, so eight neighbouring lanes read one whole 128 B line.  The chunk's
+  // 4 NS such loads are split evenly over the four waves (NS each).  The descriptor ends after column N - 1
+  // (the column is in the per-lane offset, which is what the bounds check of a raw buffer looks
+  // at), so columns that pad the pass up to 64 read as zero.
+  // In LDS a K tile is four 1 KB blocks, one per (32-column block cb, 16-k step ks), of 64 slots of
+  // 16 B: the B fragment of MFMA lane 32 h + c sits in slot 32 h + (c ^ (4 ks + 2 h + 8 tp)), tp = the
+  // tile's parity.  The MFMA read (16 neighbouring lanes: 16 neighbouring slots in some order) and
+  // the store of a loaded register (the 8 k chunks of a column: 8 different 16 B bank groups) are both
+  // free of bank conflicts.
+  const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)p.X, 0, (int)(p.N * p.K * 2u), kBufferFlags);
+  const uint32_t c8 = (uint32_t)lane >> 3, ch = (uint32_t)lane & 7u;
+  const uint32_t colgrp_bytes = 16u * p.K;  // eight columns further
+  // This wave's loads of a chunk are q = wave * NS + e, e < NS: tile pair q >> 3, column group q & 7;
+  // NS is 4 or 8, so the pair and the group's upper part are the wave's (folded into the per-lane
+  // offsets below) and e only adds to the group.  Everything that may leave the buffer - the column and,
+  // for the chunk requested past the end of K, the k offset - is in the per-lane offset.
+  const uint32_t pair_w = (wave * NS) >> 3, grp_w = (wave * NS) & 7u;
+  const uint32_t xg_lane = ((p.n0 + 8u * grp_w + c8) * p.K + pair_w * 64u + ch * 8u) * 2u;  // + e column groups + the chunk's k
+  // LDS byte address of this lane's store of load e, by e & 3 (the column group inside its 32-column
+  // block), in the chunk to fill: k chunk ch of the tile pair = tile parity ch >> 2, step (ch >> 1) & 1,
+  // lane half ch & 1
+  uint32_t xw_addr[4];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      const bool wanted = xti < k1 && (uint32_t)nb < xvalid;
-      if (FLS_ABLATE & 256) xq[nb] = u32x4{base, 1u, 2u, 3u};
-      else xq[nb] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, wanted ? base + nb * 1024u : 0xffffff00u, 0, 0);  // else: 0
+  for (int e3 = 0; e3 < 4; ++e3)
+    xw_addr[e3] = (uint32_t)(uintptr_t)lds + kChunkBytes + pair_w * 8192u + (grp_w >> 2) * 2048u + (ch >> 2) * 4096u +
+                  ((ch >> 1) & 1u) * 1024u + (32u * (ch & 1u) + ((8u * e3 + c8) ^ (2u * ch))) * 16u;
+  // LDS byte address of this lane's fragment read by tile parity and 16-k step, in the chunk in use and in the other one
+  uint32_t xr_addr[2][kSteps16], xr_other[2][kSteps16];
+  {
+    const uint32_t c = (uint32_t)lane & 31u, h = (uint32_t)lane >> 5;
+#pragma unroll
+    for (int tp = 0; tp < 2; ++tp)
+#pragma unroll
+      for (int ks = 0; ks < kSteps16; ++ks) {
+        xr_addr[tp][ks] = (uint32_t)(uintptr_t)lds + ks * 1024u + (32u * h + (c ^ (4u * ks + 2u * h + 8u * tp))) * 16u;
+        xr_other[tp][ks] = xr_addr[tp][ks] + kChunkBytes;
+      }
+  }
+  typedef __attribute__((address_space(3))) u32x4* lds_v4_ptr;
+  typedef __attribute__((address_space(3))) const half8* lds_h8_ptr;
+  // loads e0, e0 + 1 of this wave's share of the chunk that starts at K tile kt
+  auto xload2 = [&](u32x4(&xs)[NS], int e0, uint32_t kt) {
+#pragma unroll
+    for (int e = e0; e < e0 + 2; ++e)
+      xs[e] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, xg_lane + (uint32_t)e * colgrp_bytes + kt * 64u, 0, 0);
+  };
+  // ... and their stores into the chunk to fill
+  auto xstore2 = [&](const u32x4(&xs)[NS], int e0) {
+#pragma unroll
+    for (int e = e0; e < e0 + 2; ++e) *(lds_v4_ptr)(uintptr_t)(xw_addr[e & 3] + (uint32_t)(e >> 2) * 2048u) = xs[e];
+  };
+  // B fragment (column block cb, step ks) of tile `it` (0 .. NS - 1) of the chunk in use (`other`: of the
+  // other chunk, the next body's)
+  auto xfrag = [&](int it, int cb, int ks, bool other) {
+    const uint32_t base = other ? xr_other[it & 1][ks] : xr_addr[it & 1][ks];
+    return *(lds_h8_ptr)(uintptr_t)(base + (uint32_t)it * 4096u + (uint32_t)cb * 2048u);
+  };
+  // all four waves have stored their part of the next chunk and are done reading the present one
+  auto chunk_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+  auto flip_chunks = [&]() {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      xw_addr[j] ^= kChunkBytes;
+      xr_addr[j >> 1][j & 1] ^= kChunkBytes;
+      xr_other[j >> 1][j & 1] ^= kChunkBytes;
     }
-    ++xti;
   };
 
-  // TileOffsets: a window of 64 entries in a VGPR (lane i = entry base + i), replaced once per
+  // ---- W
+  // TileOffsets: a window of 64 entries in a VGPR (lane i = entry first + i), replaced once per
   // body by the window that was requested a body earlier - an unconditional load per NS tiles, so
-  // stepping from tile to tile costs v_readlane and no wait.
+  // stepping from tile to tile costs v_readlane (with a constant lane) and no wait.
   const uint32_t* offs = p.offs;
   auto window_at = [&](uint32_t first) {
     const uint32_t idx = first + (uint32_t)lane;
     return offs[idx < T ? idx : T];
   };
-  uint32_t wbase = t0, window = window_at(t0);
-  uint32_t ti = t0;  // next tile to request
-  auto issue = [&](u32x4(&s)[R], uint32_t& begin, uint32_t& end) {
-    begin = (uint32_t)__builtin_amdgcn_readlane((int)window, (int)(ti - wbase));
-    end = (uint32_t)__builtin_amdgcn_readlane((int)window, (int)(ti + 1 - wbase));
-    uint32_t n = end - begin;
+  uint32_t window = window_at(t0);
+  // Request of the tile whose offsets are lanes i, i + 1 of the window, and which is tile `rel` of
+  // the run: n = words staged (0 past the run: nothing loaded, nothing extracted).
+  auto issue = [&](u32x4(&s)[R], uint32_t& n, int i, uint32_t rel) {
+    const uint32_t begin = (uint32_t)__builtin_amdgcn_readlane((int)window, i);
+    const uint32_t end = (uint32_t)__builtin_amdgcn_readlane((int)window, i + 1);
+    n = end - begin;
     if (n > R * 256u) n = R * 256u;
-    if (ti >= t1) {  // past the run: nothing to load, nothing to extract
-      n = 0;
-      end = begin;
-    }
+    if (rel >= ntiles) n = 0;
     const __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void*)(p.words + begin), 0, (int)(n * 4u), kBufferFlags);
 #pragma unroll
@@ -142,7 +247,6 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
       if (FLS_ABLATE & 32) s[r] = u32x4{(uint32_t)lane, 1u, 2u, 3u};
       else s[r] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (r * 64 + lane) * 16, 0, kAuxNonTemporal);
     }
-    ++ti;
   };
 
   // extract (Alg. 2), branch-free so that a step is one basic block: lanes past the end of the
@@ -151,8 +255,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   // later re-zeroing needs.  (No tile has more than R * 256 words here: see `densest` below.)
   typedef __attribute__((address_space(3))) uint16_t* lds_u16_ptr;
   const uint32_t tile_addr = (uint32_t)(uintptr_t)tile;  // LDS addresses are the low 32 bits
-  auto extract = [&](u32x4(&s)[R], uint32_t begin, uint32_t end) {
-    const uint32_t n = end - begin;
+  auto extract = [&](u32x4(&s)[R], uint32_t n) {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const uint32_t base = (r * 64 + lane) * 4u < n ? tile_addr : tile_addr + (uint32_t)kTileBytes;
@@ -167,156 +270,200 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
     }
   };
 
-  const unsigned char* frag = tile + ((lane >> 4) * kTileM + (lane & 15)) * 16;
+  // A fragment (32-row block rb, 16-k step ks): row 32 rb + (lane & 31), k chunk 2 ks + (lane >> 5) of the
+  // [k chunk][row][8] tile
+  const unsigned char* frag = tile + ((lane >> 5) * kTileM + (lane & 31)) * 16;
+  auto afrag = [&](int rb, int ks) { return *(const half8*)(frag + ks * 4096 + rb * 512); };
 
   // rst_smem.  Sparse tiles (R <= 4: at most 1024 words) are re-zeroed by storing zeros where
   // their words went - as many 2 B stores as the extraction - instead of clearing all 8 KB.
   constexpr bool kUnscatter = R <= 4;
-  auto unscatter = [&](const u32x4(&s)[R]) {
-#pragma unroll
-    for (int r = 0; r < R; ++r)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) *(lds_u16_ptr)(uintptr_t)s[r][j] = (uint16_t)0;
+
+  // One step = one tile t, tile `it` of its body.  On entry the tile's A fragments are in `fa` and its B
+  // fragments in `fb` (both read from LDS during the step before), its words - LDS addresses by now -
+  // in stage `cur`.  The 16 MFMAs of tile t are issued one by one with the step's other work dealt
+  // out between them in a fixed order (a wave alone on its SIMD issues in order: what stands between
+  // two MFMAs runs in the shadow of the first): this wave's part of the X chunk of the next body (loads
+  // in the first half of a body, stores into LDS in the second), re-zero tile t, extract tile t + 1
+  // (stage `nxt`), read its fragments into `fan` / `fbn`, refill stage `cur`.  LDS executes a wave's
+  // operations in order, so no wait separates re-zeroing, extraction and the fragment reads; the
+  // MFMAs never wait for anything issued in their own step.  The last step of a body meets the other
+  // waves before it reads B fragments from the chunk they filled together.
+  constexpr int kFragsA = kSteps16 * kRowBlocks32, kFragsB = kSteps16 * kColBlocks32;
+  auto step = [&](auto it_, u32x4(&cur)[R], uint32_t& cn, uint32_t rel, u32x4(&nxt)[R], uint32_t nn, u32x4(&xs)[NS],
+                  uint32_t kt_next, const half8(&fa)[kFragsA], const half8(&fb)[kFragsB], half8(&fan)[kFragsA],
+                  half8(&fbn)[kFragsB]) {
+    constexpr int it = decltype(it_)::value;
+    constexpr int kZ = kUnscatter ? 4 * R : kTileBytes / 1024;  // re-zeroing operations
+    constexpr int kE = 5 * R;                                   // extraction: per round a base select and four words
+    constexpr int kOps = 1 + kZ + kE + 1 + kFragsA + kFragsB + 1;
+    constexpr int kMfmas = kSteps16 * kRowBlocks32 * kColBlocks32;
+    uint32_t ebase = 0;
+    auto other = [&](auto o_) {
+      constexpr int o = decltype(o_)::value;
+      if constexpr (o == 0) {
+        if (FLS_ABLATE & 256) {
+        } else if constexpr (it < NS / 2) {
+          xload2(xs, 2 * it, kt_next);
+        } else {
+          xstore2(xs, 2 * (it - NS / 2));
+        }
+      } else if constexpr (o < 1 + kZ) {
+        constexpr int z = o - 1;
+        if (FLS_ABLATE & 8) {
+        } else if constexpr (kUnscatter) {
+          *(lds_u16_ptr)(uintptr_t)cur[z / 4][z % 4] = (uint16_t)0;
+        } else {
+          *(u32x4*)(tile + z * 1024 + lane * 16) = zero4;
+        }
+      } else if constexpr (o < 1 + kZ + kE) {
+        constexpr int r = (o - 1 - kZ) / 5, j = (o - 1 - kZ) % 5 - 1;
+        if constexpr (j < 0) {
+          ebase = (r * 64 + lane) * 4u < nn ? tile_addr : tile_addr + (uint32_t)kTileBytes;
+        } else {
+          const uint32_t w = nxt[r][j];
+          const uint32_t addr = scatter_addr(w, ebase);
+          if (FLS_ABLATE & 4) asm volatile("" ::"v"(w));
+          else *(lds_u16_ptr)(uintptr_t)addr = (uint16_t)(w >> 16);
+          nxt[r][j] = addr;
+        }
+      } else if constexpr (o == 1 + kZ + kE) {
+        if constexpr (it == NS - 1) chunk_barrier();
+      } else if constexpr (o < 2 + kZ + kE + kFragsA) {
+        constexpr int j = o - 2 - kZ - kE;  // step-major: the fragments of the first 16 k come first
+        if (FLS_ABLATE & 16) fan[j] = fb[j % kFragsB];
+        else fan[j] = afrag(j % kRowBlocks32, j / kRowBlocks32);
+      } else if constexpr (o < 2 + kZ + kE + kFragsA + kFragsB) {
+        constexpr int j = o - 2 - kZ - kE - kFragsA;
+        if (FLS_ABLATE & 256) fbn[j] = fb[j];
+        else fbn[j] = xfrag((it + 1) % NS, j % kColBlocks32, j / kColBlocks32, it == NS - 1);
+      } else {
+        issue(cur, cn, it, rel);
+      }
+    };
+    // MFMA s: 16-k step s / 8, row block (s % 8) / 2, column block s % 2 - the two MFMAs of an
+    // accumulator lie eight apart
+    static_for<0, kMfmas>([&](auto s_) {
+      constexpr int s = decltype(s_)::value;
+      constexpr int ks = s / (kRowBlocks32 * kColBlocks32), rb = (s / kColBlocks32) % kRowBlocks32, cb = s % kColBlocks32;
+      if (FLS_ABLATE & 2) acc[rb][cb][0] += (float)fa[ks * kRowBlocks32 + rb][0] * (float)fb[ks * kColBlocks32 + cb][0];
+      else mfma_in_place(acc[rb][cb], fa[ks * kRowBlocks32 + rb], fb[ks * kColBlocks32 + cb]);
+      static_for<s * kOps / kMfmas, (s + 1) * kOps / kMfmas>(other);
+    });
   };
 
-  // One tile, whose words stage `cur` still holds (as LDS addresses by now) and which the step
-  // before extracted into LDS: the X stage that step used is refilled, the tile's A fragments are
-  // read, the tile is re-zeroed behind the reads, stage `cur` is refilled, the next tile (stage
-  // `nxt`) is extracted, and the MFMAs run spread between those instructions.
-  auto step = [&](u32x4(&cur)[R], uint32_t& cb, uint32_t& ce, u32x4(&nxt)[R], uint32_t nb_, uint32_t ne_,
-                  u32x4(&xfill)[NB], const u32x4(&xuse)[NB]) {
-    half8 fa[kRowBlocks], fb[NB];
-    xissue(xfill);
+  // B fragments straight from the caller's X, for the plain loop: lane 32 h + c takes column c of a
+  // 32-column block, k chunk h of a 16-k step
+  const uint32_t xd_lane = ((p.n0 + ((uint32_t)lane & 31u)) * p.K + ((uint32_t)lane >> 5) * 8u) * 2u;
+  // One tile the plain way: words straight from memory into LDS, fragments, re-zero, MFMAs.
+  auto plain_tile = [&](uint32_t t, uint32_t kt) {
+    const uint32_t begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)offs[t]);
+    const uint32_t end = (uint32_t)__builtin_amdgcn_readfirstlane((int)offs[t + 1]);
+    for (uint32_t i = begin + (uint32_t)lane * 4u; i < end; i += 256u) {
+      const u32x4 w = *(const u32x4*)(p.words + i);
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) fb[nb] = __builtin_bit_cast(half8, xuse[nb]);
-#pragma unroll
-    for (int j = 0; j < kRowBlocks; ++j) {
-      if (FLS_ABLATE & 16) fa[j] = fb[j % NB];
-      else fa[j] = *(const half8*)(frag + j * 256);
+      for (int j = 0; j < 4; ++j) *(uint16_t*)(tile + ((w[j] & 0xffffu) << 1)) = (uint16_t)(w[j] >> 16);
     }
-    if (FLS_ABLATE & 8) {
-    } else if constexpr (kUnscatter) {
-      unscatter(cur);
-    } else {
+    half8 fa[kFragsA], fb[kFragsB];
 #pragma unroll
-      for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
-    }
-    issue(cur, cb, ce);
-    extract(nxt, nb_, ne_);
+    for (int j = 0; j < kFragsB; ++j)
+      fb[j] = __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(
+                                            xrsrc, xd_lane + (j % kColBlocks32) * 4u * colgrp_bytes + kt * 64u + (j / kColBlocks32) * 32u, 0, 0));
 #pragma unroll
-    for (int j = 0; j < kRowBlocks; ++j)
+    for (int j = 0; j < kFragsA; ++j) fa[j] = afrag(j % kRowBlocks32, j / kRowBlocks32);
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        if (FLS_ABLATE & 2) acc[j][nb][0] += (float)fa[j][0] * (float)fb[nb][0];
-        else acc[j][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[j], fb[nb], acc[j][nb], 0, 0, 0);
-      }
-    // asks the scheduler for: one MFMA, then up to three instructions of the other kinds
+    for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
 #pragma unroll
-    for (int i = 0; i < kRowBlocks * NB; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002 | 0x004 | 0x010 | 0x080, 3, 0);
-    }
+    for (int ks = 0; ks < kSteps16; ++ks)
+#pragma unroll
+      for (int rb = 0; rb < kRowBlocks32; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < kColBlocks32; ++cb)
+          acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ks * kRowBlocks32 + rb], fb[ks * kColBlocks32 + cb], acc[rb][cb], 0, 0, 0);
   };
 
   // The launcher picks R from the header the host remembers for this blob address.  If the memory
   // holds a denser blob by now (one written there without the library's knowing), the ring cannot
-  // stage its tiles: the whole grid then takes a plain path - tile by tile, words straight from
-  // memory into LDS, X fragments from the packed copy - which is slow and right.
+  // stage its tiles: the whole grid then takes the plain loop for all its tiles, which is slow and right.
   const uint32_t densest = offs[kHeaderMaxTileWords - kHeaderWords];
-  if (densest > R * 256u) {
-    for (uint32_t t = t0; t < t1; ++t) {
-      const uint32_t begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)offs[t]);
-      const uint32_t end = (uint32_t)__builtin_amdgcn_readfirstlane((int)offs[t + 1]);
-      for (uint32_t i = begin + (uint32_t)lane * 4u; i < end; i += 256u) {
-        const u32x4 w = *(const u32x4*)(p.words + i);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) *(uint16_t*)(tile + ((w[j] & 0xffffu) << 1)) = (uint16_t)(w[j] >> 16);
-      }
-      const uint32_t kt = k0 + (t - t0);
-      half8 fa[kRowBlocks], fb[NB];
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb) {
-        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(
-            xrsrc, (uint32_t)nb < xvalid ? kt * xblocks * 1024u + xlane + nb * 1024u : 0xffffff00u, 0, 0);
-        fb[nb] = __builtin_bit_cast(half8, v);
-      }
-#pragma unroll
-      for (int j = 0; j < kRowBlocks; ++j) fa[j] = *(const half8*)(frag + j * 256);
-#pragma unroll
-      for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
-#pragma unroll
-      for (int j = 0; j < kRowBlocks; ++j)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-          acc[j][nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[j], fb[nb], acc[j][nb], 0, 0, 0);
-    }
-  } else {
-    // Rings: NS tiles of W words in flight; X fragments XS - 1 tiles ahead (they come from L2 and
-    // ride behind the words in the same in-order load queue).  Prologue: both rings filled, first
-    // tile in LDS.
+  uint32_t kplain = k0;  // first K tile of the plain loop
+  if (densest <= R * 256u && bodies > 0) {
+    kplain = k1;
+    // Prologue: the first chunk of X into LDS, the ring of words filled, the first tile in LDS and
+    // its fragments in registers.  (The next window of offsets is requested before the ring's loads,
+    // as in the loop: the wait for a window then never covers the ring loads issued after it.)
     u32x4 s[NS][R];
-    uint32_t sb[NS], se[NS];
-    u32x4 xq[XS][NB];
-#pragma unroll
-    for (int i = 0; i < XS - 1; ++i) xissue(xq[i]);
-#pragma unroll
-    for (int i = 0; i < NS; ++i) issue(s[i], sb[i], se[i]);
+    uint32_t sn[NS];
+    u32x4 xs[NS];
     uint32_t next_window = window_at(t0 + NS);
-    extract(s[0], sb[0], se[0]);
+#pragma unroll
+    for (int e = 0; e < NS; e += 2) xload2(xs, e, k0);
+#pragma unroll
+    for (int i = 0; i < NS; ++i) issue(s[i], sn[i], i, (uint32_t)i);
+    flip_chunks();  // the stores below fill the chunk the loop starts with
+#pragma unroll
+    for (int e = 0; e < NS; e += 2) xstore2(xs, e);
+    flip_chunks();
+    extract(s[0], sn[0]);
+    chunk_barrier();
+    half8 fa0[kFragsA], fa1[kFragsA], fb0[kFragsB], fb1[kFragsB];
+#pragma unroll
+    for (int j = 0; j < kFragsA; ++j) fa0[j] = afrag(j % kRowBlocks32, j / kRowBlocks32);
+#pragma unroll
+    for (int j = 0; j < kFragsB; ++j) fb0[j] = xfrag(0, j % kColBlocks32, j / kColBlocks32, false);
+    uint32_t rel = NS;       // first tile the body's refills ask for
+    uint32_t kt_next = k0;   // first K tile of the chunk the body loads
     for (uint32_t body = 0; body < bodies; ++body) {
-      // refills of this body ask for tiles t0 + NS * body + NS ... + 2 NS - 1: inside the window
-      // that starts at t0 + NS * (body + 1)
+      // refills of this body ask for tiles rel ... rel + NS - 1 of the run: lanes 0 ... NS of the window
+      // that starts at tile t0 + rel
       window = next_window;
-      wbase = t0 + NS * (body + 1);
-      next_window = window_at(t0 + NS * (body + 2));
-#pragma unroll
-      for (int i = 0; i < NS; ++i) {
-        const int i1 = (i + 1) % NS;  // stage of the next tile
-        step(s[i], sb[i], se[i], s[i1], sb[i1], se[i1], xq[(i + XS - 1) % XS], xq[i % XS]);
-      }
+      next_window = window_at(t0 + rel + NS);
+      kt_next += NS;
+      static_for<0, NS / 2>([&](auto h_) {
+        constexpr int i = 2 * decltype(h_)::value, i1 = i + 1, i2 = (i + 2) % NS;
+        step(std::integral_constant<int, i>{}, s[i], sn[i], rel + i, s[i1], sn[i1], xs, kt_next, fa0, fb0, fa1, fb1);
+        step(std::integral_constant<int, i1>{}, s[i1], sn[i1], rel + i1, s[i2], sn[i2], xs, kt_next, fa1, fb1, fa0, fb0);
+      });
+      rel += NS;
+      flip_chunks();
     }
+    // the last MFMAs' results are read by ordinary instructions next: the accumulators are asm
+    // operands, so the wait states between the two are given here by hand
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
   }
+  // K tiles that fill no body (and everything, for a blob denser than the ring was picked for)
+  if (active)
+    for (uint32_t kt = kplain; kt < ktail; ++kt) plain_tile(band * KT + kt, kt);
+  if (!active) return;
 
-  // The two halves of the K slice meet in LDS: the waves of the second half leave their
-  // accumulators there, the waves of the first half add them to their own and write the band's
-  // result for the slice - half as many partial sums in memory as waves.
-  float4v* meet = (float4v*)(lds + kWideWaves * kWideTileLds) + (wave & 1u) * (NB * kRowBlocks * 64) + lane;
-  if (half == 1) {
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-      for (int rb = 0; rb < kRowBlocks; ++rb) meet[(nb * kRowBlocks + rb) * 64] = acc[rb][nb];
-  }
-  __syncthreads();
-  if (half == 1 || !active) return;
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-    for (int rb = 0; rb < kRowBlocks; ++rb) acc[rb][nb] += meet[(nb * kRowBlocks + rb) * 64];
+  // The band's result for the slice: to C directly when the slice is all of K, else to the
+  // partial-sum area [band][slice] that a second, small kernel adds up in slice order.
   if (p.S == 1) {
-    OutParams o;
-    o.C = p.C;
-    o.M = p.M;
-    o.N = p.N;
-    o.n0 = p.n0;
-    store_band<NB>(o, acc, band, lane);
+    store_band32(p.C, p.M, p.N, p.n0, acc, band, lane);
   } else {
+    // [band][slice][column block][row block][q][lane] float4: rows 8 q + 4 (lane >> 5) + (0..3) of the row block
     float4v* dst = (float4v*)p.parts + ((size_t)(band * p.S + slice) * (NB * kRowBlocks)) * 64 + lane;
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+    for (int cb = 0; cb < kColBlocks32; ++cb)
 #pragma unroll
-      for (int rb = 0; rb < kRowBlocks; ++rb) dst[(nb * kRowBlocks + rb) * 64] = acc[rb][nb];
+      for (int rb = 0; rb < kRowBlocks32; ++rb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          dst[((cb * kRowBlocks32 + rb) * 4 + q) * 64] =
+              float4v{acc[rb][cb][4 * q], acc[rb][cb][4 * q + 1], acc[rb][cb][4 * q + 2], acc[rb][cb][4 * q + 3]};
   }
 }
 
-// Adds the S partial results of every band in slice order, converts, writes C.  One wave per
-// (band, column block, row block): S loads of 16 B per lane, all issued before the first is used.
+// Adds the S partial results of every band in slice order, converts, writes C.  One wave per 1 KB
+// unit of a band's partial result (32 units): S loads of 16 B per lane, all issued before the first is
+// used.  A unit is (column block of 16, row block of 16) in the 16x16 accumulator layout of the dense
+// pass, (column block of 32, row block of 32, q) in the 32x32 layout of the sparse pass (LAYOUT32).
+template <bool LAYOUT32>
 __global__ __launch_bounds__(256) void wide_reduce_kernel(WideParams p) {
   const uint32_t unit = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (unit >= p.bands * (kWideNB * kRowBlocks)) return;
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t band = unit / (kWideNB * kRowBlocks), sub = unit - band * (kWideNB * kRowBlocks);
-  const uint32_t nb = sub / kRowBlocks, rb = sub - nb * kRowBlocks;
   const float4v* src = (const float4v*)p.parts + ((size_t)band * p.S * (kWideNB * kRowBlocks) + sub) * 64 + lane;
   float4v sum = {0.f, 0.f, 0.f, 0.f};
   for (uint32_t s0 = 0; s0 < p.S; s0 += 8) {
@@ -330,48 +477,61 @@ __global__ __launch_bounds__(256) void wide_reduce_kernel(WideParams p) {
     for (int j = 0; j < 8; ++j)
       if (s0 + j < p.S) sum += v[j];
   }
-  const uint32_t n = p.n0 + nb * 16 + (lane & 15u);
+  uint32_t n, row;
+  if (LAYOUT32) {
+    n = p.n0 + (sub / 16u) * 32u + (lane & 31u);
+    row = ((sub / 4u) % 4u) * 32u + (sub % 4u) * 8u + (lane >> 5) * 4u;
+  } else {
+    n = p.n0 + (sub / kRowBlocks) * 16u + (lane & 15u);
+    row = (sub % kRowBlocks) * 16u + (lane >> 4) * 4u;
+  }
   if (n < p.N) {
     half4 h;
 #pragma unroll
     for (int r = 0; r < 4; ++r) h[r] = (_Float16)sum[r];
-    *(half4*)(p.C + (size_t)n * p.M + band * kTileM + rb * 16 + (lane >> 4) * 4) = h;
+    *(half4*)(p.C + (size_t)n * p.M + band * kTileM + row) = h;
   }
 }
 
-template <int R, int NS, int XS>
-static hipError_t launch_wide_variant(const WideParams& p, int grid, hipStream_t stream) {
+template <int R, int NS>
+static hipError_t launch_wide_variant(WideParams p, int cus, hipStream_t stream) {
   static bool attr_done = false;
+  constexpr int kLds = wide_lds_bytes<NS>();
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)spmm_wide_kernel<R, NS, XS>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kWideLdsBytes);
+    hipError_t e = hipFuncSetAttribute((const void*)spmm_wide_kernel<R, NS>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL((spmm_wide_kernel<R, NS, XS>), dim3(grid), dim3(kWideWaves * 64), kWideLdsBytes, stream, p);
-  return hipGetLastError();
+  const uint32_t quads = (p.bands + 3u) / 4u;
+  p.S = wide_quad_slices(p.bands, p.KT, cus, NS);
+  hipLaunchKernelGGL((spmm_wide_kernel<R, NS>), dim3(quads * p.S), dim3(kWideWaves * 64), kLds, stream, p);
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess && p.S > 1) e = launch_wide_reduce(p, true, stream);
+  return e;
 }
 
-// X (all N columns of the call) into fragment order, once per call.
+// X (all N columns of the call) into fragment order, once per call of the dense 64-column pass.
 hipError_t launch_xpack(const _Float16* X, _Float16* xpack, uint32_t K, uint32_t N, hipStream_t stream) {
   const uint32_t blocks = (N + 15u) / 16u, units = ((K / kTileK + 1u) / 2u) * blocks;
   hipLaunchKernelGGL(xpack_kernel, dim3((units + 3) / 4), dim3(256), 0, stream, X, xpack, K, N, units, blocks);
   return hipGetLastError();
 }
 
-hipError_t launch_wide_reduce(const WideParams& p, hipStream_t stream) {
+hipError_t launch_wide_reduce(const WideParams& p, bool layout32, hipStream_t stream) {
   const uint32_t units = p.bands * (kWideNB * kRowBlocks);
-  hipLaunchKernelGGL(wide_reduce_kernel, dim3((units + 3) / 4), dim3(256), 0, stream, p);
+  if (layout32) hipLaunchKernelGGL(wide_reduce_kernel<true>, dim3((units + 3) / 4), dim3(256), 0, stream, p);
+  else hipLaunchKernelGGL(wide_reduce_kernel<false>, dim3((units + 3) / 4), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 
-// One 64-column pass starting at column n0; `xpack` holds all N columns in fragment order.
+// One 64-column pass starting at column n0.
 hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, hipStream_t stream) {
   WideParams p;
   p.offs = a.offs;
   p.words = a.words;
   p.W = nullptr;
-  p.Xp = a.xpack;
+  p.X = a.X;
+  p.Xp = nullptr;
   p.C = a.C;
   p.parts = a.parts;
   p.M = a.M;
@@ -380,20 +540,14 @@ hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, hipStream_t stream
   p.n0 = n0;
   p.KT = a.K / kTileK;
   p.bands = a.M / kTileM;
-  const uint32_t pairs = (p.bands + 1u) / 2u;
-  p.S = wide_pair_slices(p.bands, p.KT, a.num_cus);
-  const int grid = (int)(pairs * p.S);
-  hipError_t e;
-  // rounds of 256 words staged per tile; the ring is 8 tiles deep while the registers allow; X fragments 3 tiles ahead
-  if (a.max_tile_words <= 2 * 256) e = launch_wide_variant<2, 8, 4>(p, grid, stream);
-  else if (a.max_tile_words <= 3 * 256) e = launch_wide_variant<3, 8, 4>(p, grid, stream);
-  else if (a.max_tile_words <= 4 * 256) e = launch_wide_variant<4, 8, 4>(p, grid, stream);
-  else if (a.max_tile_words <= 6 * 256) e = launch_wide_variant<6, 4, 4>(p, grid, stream);
-  else if (a.max_tile_words <= 8 * 256) e = launch_wide_variant<8, 4, 4>(p, grid, stream);
-  else e = launch_wide_variant<10, 4, 4>(p, grid, stream);
-  if (e != hipSuccess) return e;
-  if (p.S > 1) e = launch_wide_reduce(p, stream);
-  return e;
+  p.S = 1;
+  // rounds of 256 words staged per tile; the ring is 8 tiles deep while the registers allow
+  if (a.max_tile_words <= 2 * 256) return launch_wide_variant<2, 8>(p, a.num_cus, stream);
+  if (a.max_tile_words <= 3 * 256) return launch_wide_variant<3, 8>(p, a.num_cus, stream);
+  if (a.max_tile_words <= 4 * 256) return launch_wide_variant<4, 8>(p, a.num_cus, stream);
+  if (a.max_tile_words <= 6 * 256) return launch_wide_variant<6, 4>(p, a.num_cus, stream);
+  if (a.max_tile_words <= 8 * 256) return launch_wide_variant<8, 4>(p, a.num_cus, stream);
+  return launch_wide_variant<10, 4>(p, a.num_cus, stream);
 }
 
 }  // namespace fls
