@@ -141,6 +141,75 @@ def run_sweep(args):
         raise SystemExit(f"sweep: a point is off the oracle by {worst:.3g} (tolerance 2e-3)")
 
 
+def run_crossover(args):
+    """The study of non-skinny shapes (Sec. 6.2): the 12288 x 12288 matrix at 70 / 80 / 90 % sparsity for N from 64 to
+    8192, fls_spmm against the own dense GEMM and the vendor library's, to find where loading sparse and computing
+    dense stops paying.  One JSON line per point (not the bench line).  C is checked against the oracle on all
+    columns up to N = 512 and on 256 sampled columns beyond."""
+    import torch
+
+    import fls_workloads as wl
+    import oracle
+    import paper_2309_10285_amd as fls
+
+    fls.lib()
+    M, K = wl.SWEEP_M, wl.SWEEP_K
+    Ns = (64, 128, 256, 512, 1024, 2048, 4096, 8192)
+    W32 = wl.gen_weights_f32(M, K, wl.SWEEP_SEED)
+    out = open(args.out, "w") if args.out else None
+
+    def emit(rec):
+        line = json.dumps(rec)
+        print(line, flush=True)
+        if out:
+            out.write(line + "\n")
+            out.flush()
+
+    def steps_for(N):  # a call takes up to some milliseconds here
+        return max(10, min(args.steps, 40000 // N))
+
+    Xs = {N: wl.gen_x(N, K, wl.SWEEP_SEED + 2) for N in Ns}
+    Xd = {N: torch.from_numpy(Xs[N].view(np.float16)).cuda() for N in Ns}
+    fls.ensure_workspace(M, K, max(Ns))
+    Wd = torch.from_numpy(wl.dense_bits(W32).view(np.float16)).cuda()
+    dense = [Wd, Wd.clone(), Wd.clone(), Wd.clone()]
+    dense_ms, vendor_ms = {}, {}
+    for N in Ns:
+        D = torch.empty((N, M), dtype=torch.float16, device="cuda")
+        dense_ms[N], _ = _time_loop([fls.prepare_dense_gemm(w, Xd[N], D, M, K, N) for w in dense], steps_for(N), 5)
+        vendor_ms[N], _ = _time_loop([lambda w=w, x=Xd[N], v=D: torch.matmul(x, w.t(), out=v) for w in dense], steps_for(N), 5)
+        emit({"point": f"dense-N{N}", "N": N, "own_dense_us": round(dense_ms[N] * 1e3, 1),
+              "vendor_gemm_us": round(vendor_ms[N] * 1e3, 1),
+              "vendor_TFLOPs": round(2.0 * M * K * N / vendor_ms[N] / 1e9, 1)})
+        del D
+    del dense, Wd
+    worst = 0.0
+    g = np.random.Generator(np.random.Philox(99))
+    for beta in (0.7, 0.8, 0.9):
+        Wb = wl.prune_uniform(W32, beta, wl.SWEEP_SEED + 1)
+        blob0, st = fls.fls_compress(torch.from_numpy(Wb.view(np.float16)).cuda())
+        blob0 = blob0.clone()
+        n_copies = max(2, -(-MIN_ROTATION_BYTES // st["bytes_total"]))
+        blobs = [blob0] + [blob0.clone() for _ in range(n_copies - 1)]
+        for N in Ns:
+            C = torch.empty((N, M), dtype=torch.float16, device="cuda")
+            ms, _ = _time_loop([fls.prepare_spmm(b, Xd[N], C, M, K, N) for b in blobs], steps_for(N), 5)
+            cols = np.arange(N) if N <= 512 else np.sort(g.choice(N, size=256, replace=False))
+            ref = oracle.ref_spmm_f64(Wb, np.ascontiguousarray(Xs[N][cols]))
+            err = float(np.abs(C.cpu().numpy()[cols].astype(np.float64) - ref).max() / np.abs(ref).max())
+            worst = max(worst, err)
+            emit({"point": f"uniform-{int(round(beta * 100))}-N{N}", "sparsity": beta, "N": N, "us": round(ms * 1e3, 1),
+                  "TFLOPs": round(2.0 * M * K * N / ms / 1e9, 1), "speedup_vs_own_dense": round(dense_ms[N] / ms, 3),
+                  "speedup_vs_vendor_gemm": round(vendor_ms[N] / ms, 3), "columns_checked": int(cols.size),
+                  "max_rel_err": err, "parity_ok": err <= PARITY_TOL})
+            del C
+        for b in blobs:
+            fls.fls_forget(b)
+        del blobs, blob0
+    if worst > PARITY_TOL:
+        raise SystemExit(f"crossover: a point is off the oracle by {worst:.3g} (tolerance {PARITY_TOL})")
+
+
 def _run_layer_on_stream(args, torch, wl, fls, side):
     N, beta = args.layer_n, 0.8
     mats = wl.decoder_layer(7168, 28672, N, beta)
@@ -361,7 +430,10 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the bench line: the 12288 x 12288 sweep (sparsity x mask x N, each with its dense pair)")
-    ap.add_argument("--out", default="", help="with --sweep: also write the lines to this file")
+    ap.add_argument("--crossover", action="store_true",
+                    help="instead of the bench line: the non-skinny study, N = 64 ... 8192 on the 12288 x 12288 matrix "
+                         "against the own and the vendor's dense GEMM")
+    ap.add_argument("--out", default="", help="with --sweep / --crossover: also write the lines to this file")
     ap.add_argument("--layer", action="store_true",
                     help="instead of the bench line: the four MatMuls of one OPT-30B-shaped decoder layer back to back, "
                          "eager and as a HIP graph")
@@ -378,6 +450,9 @@ def main():
         return
     if args.layer:
         run_layer(args)
+        return
+    if args.crossover:
+        run_crossover(args)
         return
 
     import torch

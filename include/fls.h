@@ -35,7 +35,7 @@ extern "C" {
 #define FLS_TILE_M 128u /* rows of a Tiled-CSL tile                        (Sec. 4.3.1) */
 #define FLS_TILE_K 32u  /* columns (K extent) of a Tiled-CSL tile */
 #define FLS_PAD_WORDS 4u /* a tile's run is padded to a multiple of this many words */
-#define FLS_MAX_N 256
+#define FLS_MAX_N 8192 /* the skinny case is N <= 256; wider N runs as passes of 64 columns (Sec. 6.2, non-skinny shapes) */
 #define FLS_FORMAT_VERSION 1u
 #define FLS_HEADER_BYTES 64u
 
@@ -133,7 +133,7 @@ int fls_check_workspace(fls_stream_t stream);
 
 /*
  * C = W . X with W given as a Tiled-CSL blob (the SpMM of Alg. 1): streams the blob from HBM
- * (once per 64 columns for N > 32, else once), rebuilds each tile densely in LDS, multiplies
+ * (once per 64 columns for N > 32 - N = 8192 is 128 passes over W - else once), rebuilds each tile densely in LDS, multiplies
  * with MFMA, fp32 accumulation.  Partial sums of different workgroups are added in a fixed order;
  * inside a workgroup the waves' sums are added in the order they finish unless the workgroup's
  * tiles lie in one row band (then in wave order), so two runs may differ in the last bit of an

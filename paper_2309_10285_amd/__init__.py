@@ -13,7 +13,7 @@ import os
 
 TILE_M = 128
 TILE_K = 32
-MAX_N = 256
+MAX_N = 8192
 ORDER_LOCATION = 0
 ORDER_BANK = 1
 

@@ -36,7 +36,7 @@ def test_sizes_and_bounds(fls):
     assert fls.fls_workspace_bytes(1024, 1024, 8) == (4 << 20) + 512 * 1 * 2048 * 4
     assert fls.fls_workspace_bytes(1024, 1024, 17) == (4 << 20) + 512 * 2 * 2048 * 4
     assert fls.fls_workspace_bytes(1024, 1024, 256) == (4 << 20) + 4 * 512 * 4 * 2048 * 4 + 1024 * 256 * 2
-    assert fls.fls_workspace_bytes(1000, 1024, 8) == 0 and fls.fls_workspace_bytes(1024, 1024, 257) == 0
+    assert fls.fls_workspace_bytes(1000, 1024, 8) == 0 and fls.fls_workspace_bytes(1024, 1024, 8193) == 0
     assert fls.TILE_M == 128 and fls.TILE_K == 32
 
 
@@ -48,7 +48,7 @@ def test_argument_errors_need_no_device(fls):
     assert L.fls_compress_bound(128, 32, None) == fls.EINVAL
     assert L.fls_spmm(None, None, None, 128, 32, 8, None) == fls.EINVAL
     assert L.fls_spmm(16, 16, 16, 128, 32, 0, None) == fls.EINVAL
-    assert L.fls_spmm(16, 16, 16, 128, 32, 257, None) == fls.EINVAL
+    assert L.fls_spmm(16, 16, 16, 128, 32, 8193, None) == fls.EINVAL
     assert L.fls_spmm(16, 16, 16, 127, 32, 8, None) == fls.EINVAL
     # X (K x N fp16) and C are addressed with 32-bit byte offsets: 2 K N and 2 M N must stay below 2^31
     assert L.fls_spmm(16, 16, 16, 128, 1 << 23, 256, None) == fls.EINVAL

@@ -152,6 +152,19 @@ def test_spmm_wide_n(fls, oracle_mod, N):
     assert _rel_err(C, oracle_mod.ref_spmm_f64(W, X)) <= TOL
 
 
+@pytest.mark.parametrize("N", [384, 512, 1000, 4096])
+def test_spmm_and_dense_non_skinny_n(fls, oracle_mod, N):
+    """N beyond the skinny range (Sec. 6.2, non-skinny shapes): passes of 64 columns, a ragged last one for
+    N = 1000 (40 columns: a 32-column and a 16-column pass); byte offsets into X and C reach tens of MB."""
+    W = CASES[4][1]  # 1536 x 2048, 90 % magnitude-pruned: bands cut between workgroups, K slices
+    M, K = W.shape
+    X = wl.gen_x(N, K, 700 + N)
+    ref = oracle_mod.ref_spmm_f64(W, X)
+    _, _, C = _run_spmm(fls, W, X, N)
+    assert _rel_err(C, ref) <= TOL
+    assert _rel_err(_run_dense(fls, W, X, N), ref) <= TOL
+
+
 def test_spmm_small_integers_exact(fls, oracle_mod):
     # every partial sum is an integer below 2^24: fp32 accumulation in any order is exact, and so is fp16 output
     g = np.random.Generator(np.random.Philox(4))
