@@ -9,6 +9,10 @@ from .ref import (  # noqa: F401
     half_to_double,
     ref_compress,
     ref_compress_bound,
+    ref_compress_bound_v2,
+    ref_compress_v2,
+    ref_decompress_v2,
+    ref_inspect_v2,
     ref_decompress,
     ref_inspect,
     ref_spmm_f64,

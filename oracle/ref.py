@@ -14,6 +14,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "fls_oracle.c")
+_SRC_V2 = os.path.join(_HERE, "fls_oracle_v2.c")  # format version 2 (8-bit location distances)
 _LIB = os.path.join(_HERE, "libfls_oracle.so")
 _lib = None
 
@@ -25,8 +26,9 @@ PAD_WORDS = 4
 
 def build_oracle(force=False):
     """Compile the C oracle with gcc (plain -O2, OpenMP for the row loop)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", _LIB, _SRC, "-lm"]
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_V2))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", _LIB, _SRC, _SRC_V2, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -53,6 +55,14 @@ def _load():
         lib.flso_decompress.restype = ctypes.c_int
         lib.flso_spmm_f64_rows.argtypes = [u16p, u16p, f64p, i64, i64, i64, i64, i64]
         lib.flso_spmm_f64_rows.restype = None
+        lib.flso2_compress.argtypes = [u16p, i64, i64, u32, u32, u8p, sz]
+        lib.flso2_compress.restype = sz
+        lib.flso2_compress_bound.argtypes = [i64, i64, u32, u32]
+        lib.flso2_compress_bound.restype = sz
+        lib.flso2_inspect.argtypes = [u8p, sz, u64p]
+        lib.flso2_inspect.restype = ctypes.c_int
+        lib.flso2_decompress.argtypes = [u8p, sz, u16p, i64, i64]
+        lib.flso2_decompress.restype = ctypes.c_int
         lib.flso_threads.argtypes = []
         lib.flso_threads.restype = ctypes.c_int
         _lib = lib
@@ -123,6 +133,49 @@ def ref_decompress(blob, M, K):
     rc = _load().flso_decompress(_ptr(blob, ctypes.c_uint8), blob.size, _ptr(W, ctypes.c_uint16), M, K)
     if rc != 0:
         raise ValueError(f"malformed blob (oracle code {rc})")
+    return W
+
+
+def ref_compress_v2(W, tile_m=TILE_M, tile_k=TILE_K):
+    """Dense masked W (uint16 [M, K]) -> format-version-2 blob (uint8 array): locations as 8-bit distances."""
+    W = np.ascontiguousarray(W, dtype=np.uint16)
+    M, K = W.shape
+    lib = _load()
+    need = lib.flso2_compress(_ptr(W, ctypes.c_uint16), M, K, tile_m, tile_k, None, 0)
+    if need == 0:
+        raise ValueError("unsupported geometry for the oracle compressor")
+    out = np.zeros(need, dtype=np.uint8)
+    got = lib.flso2_compress(_ptr(W, ctypes.c_uint16), M, K, tile_m, tile_k, _ptr(out, ctypes.c_uint8), need)
+    assert got == need
+    return out
+
+
+def ref_compress_bound_v2(M, K, tile_m=TILE_M, tile_k=TILE_K):
+    return int(_load().flso2_compress_bound(M, K, tile_m, tile_k))
+
+
+def ref_inspect_v2(blob):
+    blob = np.ascontiguousarray(blob, dtype=np.uint8)
+    out = np.zeros(12, dtype=np.uint64)
+    rc = _load().flso2_inspect(_ptr(blob, ctypes.c_uint8), blob.size, _ptr(out, ctypes.c_uint64))
+    d = {k: int(v) for k, v in zip(_FIELDS, out)}
+    d["rc"] = rc
+    if rc == 0:
+        d["num_tiles"] = (d["M"] // d["tile_m"]) * (d["K"] // d["tile_k"])
+        d["n_off"] = (d["num_tiles"] + 4 + 15) // 16 * 16
+        d["bytes_header"] = 64
+        d["bytes_offsets"] = 4 * d["n_off"]
+        d["bytes_nonzeros"] = 4 * d["total_words"]
+        d["bytes_total"] = 64 + d["bytes_offsets"] + d["bytes_nonzeros"]
+    return d
+
+
+def ref_decompress_v2(blob, M, K):
+    blob = np.ascontiguousarray(blob, dtype=np.uint8)
+    W = np.empty((M, K), dtype=np.uint16)
+    rc = _load().flso2_decompress(_ptr(blob, ctypes.c_uint8), blob.size, _ptr(W, ctypes.c_uint16), M, K)
+    if rc != 0:
+        raise ValueError(f"malformed version-2 blob (oracle code {rc})")
     return W
 
 
