@@ -25,7 +25,7 @@ LIB_PATH = os.path.join(_HERE, "libfls.so")
 _lib = None
 _ws_tensor = None  # keeps the registered workspace alive
 
-EXPORTS = ("fls_compress_bound", "fls_compress", "fls_inspect", "fls_workspace_bytes", "fls_set_workspace",
+EXPORTS = ("fls_compress_bound", "fls_compress", "fls_compress_bound_v2", "fls_compress_v2", "fls_inspect", "fls_workspace_bytes", "fls_set_workspace",
            "fls_check_workspace", "fls_spmm", "fls_spmm_noalloc", "fls_forget", "fls_dense_gemm", "fls_strerror")
 
 
@@ -58,6 +58,10 @@ def lib():
         L.fls_compress_bound.restype = ci
         L.fls_compress.argtypes = [vp, i64, i64, vp, sz, ci, ctypes.POINTER(FlsStats), vp]
         L.fls_compress.restype = ci
+        L.fls_compress_bound_v2.argtypes = [i64, i64, ctypes.POINTER(sz)]
+        L.fls_compress_bound_v2.restype = ci
+        L.fls_compress_v2.argtypes = [vp, i64, i64, vp, sz, ctypes.POINTER(FlsStats), vp]
+        L.fls_compress_v2.restype = ci
         L.fls_inspect.argtypes = [vp, ctypes.POINTER(FlsStats)]
         L.fls_inspect.restype = ci
         L.fls_workspace_bytes.argtypes = [i64, i64, i64]
@@ -144,6 +148,27 @@ def fls_compress(W, out=None, order_policy=ORDER_LOCATION):
     rc = lib().fls_compress(ctypes.c_void_p(W.data_ptr()), M, K, ctypes.c_void_p(out.data_ptr()), out.numel(),
                             order_policy, ctypes.byref(st), _stream())
     _check(rc, "fls_compress")
+    return out[:st.bytes_total], st.as_dict()
+
+
+def fls_compress_bound_v2(M, K):
+    out = ctypes.c_size_t(0)
+    _check(lib().fls_compress_bound_v2(M, K, ctypes.byref(out)), "fls_compress_bound_v2")
+    return out.value
+
+
+def fls_compress_v2(W, out=None):
+    """fls_compress for format version 2 (8-bit location distances, 3 bytes per nonzero)."""
+    import torch
+
+    assert W.is_cuda and W.dtype == torch.float16 and W.is_contiguous() and W.dim() == 2
+    M, K = W.shape
+    if out is None:
+        out = torch.empty(fls_compress_bound_v2(M, K), dtype=torch.uint8, device=W.device)
+    st = FlsStats()
+    rc = lib().fls_compress_v2(ctypes.c_void_p(W.data_ptr()), M, K, ctypes.c_void_p(out.data_ptr()), out.numel(),
+                               ctypes.byref(st), _stream())
+    _check(rc, "fls_compress_v2")
     return out[:st.bytes_total], st.as_dict()
 
 

@@ -12,11 +12,13 @@
 
 namespace {
 
-constexpr uint32_t kMagic = 0x31534C46u;  // "FLS1"
+constexpr uint32_t kMagic = 0x31534C46u;   // "FLS1"
+constexpr uint32_t kMagic2 = 0x32534C46u;  // "FLS2"
 
 struct BlobInfo {
   uint64_t M, K;
   uint32_t max_tile_words;
+  uint32_t version;
   uint64_t n_off;
 };
 
@@ -78,12 +80,19 @@ int parse_header(const unsigned char* h, fls_stats* st, BlobInfo* info) {
   uint64_t q[4];
   memcpy(u, h, 32);
   memcpy(q, h + 32, 32);
-  if (u[0] != kMagic || u[1] != FLS_FORMAT_VERSION) return FLS_EFORMAT;
-  if (u[2] != FLS_TILE_M || u[3] != FLS_TILE_K || u[4] != FLS_PAD_WORDS || u[5] > 1u) return FLS_EFORMAT;
+  const bool v2 = u[0] == kMagic2 && u[1] == FLS_FORMAT_VERSION_2;
+  if (!v2 && (u[0] != kMagic || u[1] != FLS_FORMAT_VERSION)) return FLS_EFORMAT;
+  if (u[2] != FLS_TILE_M || u[3] != FLS_TILE_K || u[4] != FLS_PAD_WORDS || u[5] > (v2 ? 0u : 1u)) return FLS_EFORMAT;
   if (q[0] > 0x7fffffffull || q[1] > 0x7fffffffull || !shape_ok((int64_t)q[0], (int64_t)q[1])) return FLS_EFORMAT;
   const uint64_t tiles = num_tiles((int64_t)q[0], (int64_t)q[1]);
-  if (q[2] > q[3] || q[3] > tiles * (uint64_t)(FLS_TILE_M * FLS_TILE_K) || q[3] % FLS_PAD_WORDS != 0) return FLS_EFORMAT;
-  if (u[6] > FLS_TILE_M * FLS_TILE_K || u[6] % FLS_PAD_WORDS != 0) return FLS_EFORMAT;
+  if (v2) {
+    // three words per group of four entries; a tile has at most 4096 stored elements and no bridge then
+    if (q[3] % 3 != 0 || q[3] > tiles * (uint64_t)(FLS_TILE_M * FLS_TILE_K / 4 * 3) || q[2] > q[3] / 3 * 4) return FLS_EFORMAT;
+    if (u[6] % 3 != 0 || u[6] > FLS_TILE_M * FLS_TILE_K / 4 * 3) return FLS_EFORMAT;
+  } else {
+    if (q[2] > q[3] || q[3] > tiles * (uint64_t)(FLS_TILE_M * FLS_TILE_K) || q[3] % FLS_PAD_WORDS != 0) return FLS_EFORMAT;
+    if (u[6] > FLS_TILE_M * FLS_TILE_K || u[6] % FLS_PAD_WORDS != 0) return FLS_EFORMAT;
+  }
   if (st) {
     st->format_version = u[1];
     st->tile_m = u[2];
@@ -103,6 +112,7 @@ int parse_header(const unsigned char* h, fls_stats* st, BlobInfo* info) {
     info->M = q[0];
     info->K = q[1];
     info->max_tile_words = u[6];
+    info->version = u[1];
     info->n_off = n_off_of(tiles);
   }
   return FLS_OK;
@@ -156,8 +166,8 @@ int fls_inspect(const void* header_host, fls_stats* stats_host) {
   return parse_header((const unsigned char*)header_host, stats_host, nullptr);
 }
 
-int fls_compress(const void* W_dev, int64_t M, int64_t K, void* out_dev, size_t out_capacity, int order_policy,
-                 fls_stats* stats_host, fls_stream_t stream) {
+static int compress_impl(const void* W_dev, int64_t M, int64_t K, void* out_dev, size_t out_capacity, int order_policy,
+                         uint32_t version, fls_stats* stats_host, fls_stream_t stream) {
   if (!W_dev || !out_dev || !shape_ok(M, K)) return FLS_EINVAL;
   if (order_policy != FLS_ORDER_LOCATION) return FLS_EINVAL;  // FLS_ORDER_BANK: not built yet
   if (!aligned16(W_dev) || !aligned16(out_dev)) return FLS_EALIGN;
@@ -177,6 +187,7 @@ int fls_compress(const void* W_dev, int64_t M, int64_t K, void* out_dev, size_t 
   a.M = (uint32_t)M;
   a.K = (uint32_t)K;
   a.policy = (uint32_t)order_policy;
+  a.version = version;
   {
     std::lock_guard<std::mutex> lk(g_mu);
     g_blobs.erase(out_dev);
@@ -200,6 +211,23 @@ int fls_compress(const void* W_dev, int64_t M, int64_t K, void* out_dev, size_t 
     g_blobs[out_dev] = info;
   }
   return FLS_OK;
+}
+
+int fls_compress(const void* W_dev, int64_t M, int64_t K, void* out_dev, size_t out_capacity, int order_policy,
+                 fls_stats* stats_host, fls_stream_t stream) {
+  return compress_impl(W_dev, M, K, out_dev, out_capacity, order_policy, FLS_FORMAT_VERSION, stats_host, stream);
+}
+
+int fls_compress_bound_v2(int64_t M, int64_t K, size_t* bytes_host) {
+  if (!bytes_host || !shape_ok(M, K)) return FLS_EINVAL;
+  const uint64_t tiles = num_tiles(M, K);
+  *bytes_host = (size_t)(FLS_HEADER_BYTES + 4 * n_off_of(tiles) + 3 * tiles * (uint64_t)(FLS_TILE_M * FLS_TILE_K));
+  return FLS_OK;
+}
+
+int fls_compress_v2(const void* W_dev, int64_t M, int64_t K, void* out_dev, size_t out_capacity, fls_stats* stats_host,
+                    fls_stream_t stream) {
+  return compress_impl(W_dev, M, K, out_dev, out_capacity, FLS_ORDER_LOCATION, FLS_FORMAT_VERSION_2, stats_host, stream);
 }
 
 size_t fls_workspace_bytes(int64_t M, int64_t K, int64_t N) {
@@ -302,6 +330,7 @@ int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int6
   a.K = (uint32_t)K;
   a.N = (uint32_t)N;
   a.max_tile_words = info.max_tile_words;
+  a.version = info.version;
   a.num_cus = cus;
   return fls::launch_spmm(a, (hipStream_t)stream) == hipSuccess ? FLS_OK : FLS_EHIP;
 }
@@ -313,7 +342,7 @@ int fls_spmm_noalloc(const void* Wc_dev, const fls_stats* stats_host, const void
   if (rc != FLS_OK) return rc;
   if (N > FLS_NOALLOC_MAX_N) return FLS_ESCRATCH;  // partial sums of wider calls do not fit the static array
   // the caller's stats stand in for the header read-back of fls_spmm: nothing is copied, nothing is waited for
-  if (stats_host->format_version != FLS_FORMAT_VERSION || stats_host->tile_m != FLS_TILE_M || stats_host->tile_k != FLS_TILE_K ||
+  if ((stats_host->format_version != FLS_FORMAT_VERSION && stats_host->format_version != FLS_FORMAT_VERSION_2) || stats_host->tile_m != FLS_TILE_M || stats_host->tile_k != FLS_TILE_K ||
       stats_host->M != (uint64_t)M || stats_host->K != (uint64_t)K || stats_host->num_tiles != num_tiles(M, K) ||
       stats_host->max_tile_words > FLS_TILE_M * FLS_TILE_K || stats_host->bytes_offsets != 4 * n_off_of(num_tiles(M, K)))
     return FLS_EFORMAT;
@@ -337,6 +366,7 @@ int fls_spmm_noalloc(const void* Wc_dev, const fls_stats* stats_host, const void
   a.K = (uint32_t)K;
   a.N = (uint32_t)N;
   a.max_tile_words = (uint32_t)stats_host->max_tile_words;
+  a.version = stats_host->format_version;
   a.num_cus = cus;
   return fls::launch_spmm(a, s) == hipSuccess ? FLS_OK : FLS_EHIP;
 }

@@ -177,6 +177,166 @@ hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- format version 2
+//
+// Locations as 8-bit distances, three bytes per entry (the index bytes that the footnote under the
+// paper's Eq. 2 leaves out of its model are what version 1 pays in full): a tile's entries walk a
+// location counter from 0, groups of four entries take three words (two of values, one of
+// distances).  An entry is a stored element, a bridge (value 0, distance 255) where the next
+// stored element lies more than 255 locations ahead, or padding (value 0, distance 1) up to a
+// multiple of four.  Same three kernels: count (entries per tile, bridges included; stored
+// elements summed into the header), scan, emit.
+
+constexpr uint32_t kMagic2 = 0x32534C46u;  // "FLS2"
+constexpr uint32_t kGroup = 4;              // entries per group of three words
+
+// inclusive running maximum over the 64 lanes
+__device__ __forceinline__ uint32_t wave_inclusive_max(uint32_t v, int lane) {
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t up = __shfl_up(v, d, 64);
+    if (lane >= d) v = up > v ? up : v;
+  }
+  return v;
+}
+
+// One wave walks tile (band, kt) in location order, as compress_emit_kernel does: per step a lane
+// holds the 8 halves of one (row, K-chunk) cell, i.e. 8 consecutive locations.  Returns the number
+// of entries before padding; *stored = stored elements seen by this lane.  With EMIT the entries
+// (and the padding) are written to `dst`, the tile's first group.
+template <bool EMIT>
+__device__ __forceinline__ uint32_t walk_tile_v2(const CompressParams& p, uint32_t band, uint32_t kt, int lane,
+                                                 unsigned char* dst, uint32_t* stored) {
+  auto put = [&](uint32_t e, uint32_t bits, uint32_t dist) {
+    unsigned char* g = dst + (size_t)(e >> 2) * 12u;
+    *(uint16_t*)(g + (e & 3u) * 2u) = (uint16_t)bits;
+    g[8u + (e & 3u)] = (unsigned char)dist;
+  };
+  uint32_t pos = 0;      // entries so far
+  uint32_t counter = 0;  // the location counter behind the steps done so far
+  uint32_t nz = 0;
+  for (uint32_t c = 0; c < kTileK / 8; ++c) {
+    for (uint32_t half = 0; half < kTileM / 64; ++half) {
+      const uint32_t row = half * 64 + lane;
+      const u32x4 v = *(const u32x4*)(p.W + ((size_t)band * kTileM + row) * p.K + kt * kTileK + c * 8);
+      const uint32_t mask = nonzero_mask(v);
+      const uint32_t cnt = __popc(mask);
+      const uint32_t loc0 = c * (kTileM * 8) + row * 8;
+      // the counter this lane's first element starts from: the last stored location in the lanes
+      // before it (0 stands for "none", which is also where the counter starts)
+      const uint32_t last = cnt ? loc0 + (31u - (uint32_t)__clz((int)mask)) : 0u;
+      const uint32_t run_max = wave_inclusive_max(last, lane);
+      uint32_t prev = __shfl_up(run_max, 1, 64);
+      if (lane == 0) prev = 0;
+      prev = prev > counter ? prev : counter;
+      const uint32_t first = loc0 + (uint32_t)__builtin_ctz(mask | 0x100u);
+      const uint32_t gap = first - prev;
+      const uint32_t bridges = (cnt && gap > 0u) ? (gap - 1u) / 255u : 0u;
+      const uint32_t entries = cnt + bridges;
+      const uint32_t incl = wave_inclusive_scan(entries, lane);
+      if (EMIT) {
+        uint32_t slot = pos + incl - entries, cur = prev;
+        for (uint32_t b = 0; b < bridges; ++b) {
+          put(slot++, 0u, 255u);
+          cur += 255u;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          if (mask >> e & 1u) {
+            const uint32_t bits = (e & 1) ? (v[e >> 1] >> 16) : (v[e >> 1] & 0xffffu);
+            put(slot++, bits, loc0 + e - cur);
+            cur = loc0 + e;
+          }
+        }
+      }
+      pos += __shfl(incl, 63, 64);
+      const uint32_t step_max = __shfl(run_max, 63, 64);
+      counter = step_max > counter ? step_max : counter;
+      nz += cnt;
+    }
+  }
+  if (EMIT) {
+    const uint32_t padded_entries = (pos + kGroup - 1) / kGroup * kGroup;
+    if (pos + lane < padded_entries) put(pos + lane, 0u, 1u);
+  }
+  *stored = nz;
+  return pos;
+}
+
+__global__ __launch_bounds__(256) void compress2_count_kernel(CompressParams p) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= p.T) return;
+  uint32_t nz;
+  const uint32_t entries = walk_tile_v2<false>(p, t / p.KT, t % p.KT, lane, nullptr, &nz);
+  nz = wave_sum(nz);
+  if (lane == 0) {
+    offs_of(p)[t] = entries;
+    atomicAdd((unsigned long long*)(p.out + 48), (unsigned long long)nz);  // the header's nnz (cleared before the launch)
+  }
+}
+
+__device__ __forceinline__ uint32_t words_v2(uint32_t entries) { return (entries + kGroup - 1) / kGroup * 3u; }
+
+// single workgroup of 1024 threads: entries per tile -> word offsets, guard entries, header
+__global__ __launch_bounds__(1024) void compress2_scan_kernel(CompressParams p) {
+  __shared__ unsigned long long part[1024];
+  __shared__ uint32_t longest;
+  uint32_t* offs = offs_of(p);
+  const uint32_t tid = threadIdx.x;
+  const uint32_t per = (p.T + 1023) / 1024;
+  const uint32_t a = tid * per < p.T ? tid * per : p.T, b = (tid + 1) * per < p.T ? (tid + 1) * per : p.T;
+  if (tid == 0) longest = 0;
+  __syncthreads();
+  unsigned long long s = 0;
+  uint32_t mx = 0;
+  for (uint32_t i = a; i < b; ++i) {
+    const uint32_t w = words_v2(offs[i]);
+    s += w;
+    mx = w > mx ? w : mx;
+  }
+  part[tid] = s;
+  atomicMax(&longest, mx);
+  __syncthreads();
+  for (uint32_t d = 1; d < 1024; d <<= 1) {
+    unsigned long long v = tid >= d ? part[tid - d] : 0;
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  unsigned long long run = tid ? part[tid - 1] : 0;
+  const unsigned long long total = part[1023];
+  for (uint32_t i = a; i < b; ++i) {
+    const uint32_t w = words_v2(offs[i]);
+    offs[i] = (uint32_t)run;
+    run += w;
+  }
+  for (uint32_t i = p.T + tid; i < p.n_off; i += 1024) offs[i] = (uint32_t)total;
+  if (tid == 0) {
+    uint32_t* h = (uint32_t*)p.out;
+    h[0] = kMagic2;
+    h[1] = 2u;
+    h[2] = kTileM;
+    h[3] = kTileK;
+    h[4] = kGroup;
+    h[5] = 0u;
+    h[6] = longest;
+    h[7] = 0u;
+    unsigned long long* q = (unsigned long long*)(p.out + 32);
+    q[0] = p.M;
+    q[1] = p.K;  // q[2], the stored elements, was summed by the count kernel
+    q[3] = total;
+  }
+}
+
+__global__ __launch_bounds__(256) void compress2_emit_kernel(CompressParams p) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= p.T) return;
+  uint32_t nz;
+  walk_tile_v2<true>(p, t / p.KT, t % p.KT, lane, (unsigned char*)(words_of(p) + offs_of(p)[t]), &nz);
+}
+
 static CompressParams make_params(const CompressLaunch& a) {
   CompressParams p;
   p.W = a.W;
@@ -194,15 +354,18 @@ hipError_t launch_compress_index(const CompressLaunch& a, hipStream_t stream) {
   const CompressParams p = make_params(a);
   hipError_t e = launch_fill_zero(a.out, 64, stream);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(compress_count_kernel, dim3((p.T + 3) / 4), dim3(256), 0, stream, p);
+  if (a.version == 2) hipLaunchKernelGGL(compress2_count_kernel, dim3((p.T + 3) / 4), dim3(256), 0, stream, p);
+  else hipLaunchKernelGGL(compress_count_kernel, dim3((p.T + 3) / 4), dim3(256), 0, stream, p);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL(compress_scan_kernel, dim3(1), dim3(1024), 0, stream, p);
+  if (a.version == 2) hipLaunchKernelGGL(compress2_scan_kernel, dim3(1), dim3(1024), 0, stream, p);
+  else hipLaunchKernelGGL(compress_scan_kernel, dim3(1), dim3(1024), 0, stream, p);
   return hipGetLastError();
 }
 
 hipError_t launch_compress_emit(const CompressLaunch& a, hipStream_t stream) {
   const CompressParams p = make_params(a);
-  hipLaunchKernelGGL(compress_emit_kernel, dim3((p.T + 3) / 4), dim3(256), 0, stream, p);
+  if (a.version == 2) hipLaunchKernelGGL(compress2_emit_kernel, dim3((p.T + 3) / 4), dim3(256), 0, stream, p);
+  else hipLaunchKernelGGL(compress_emit_kernel, dim3((p.T + 3) / 4), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 

@@ -15,6 +15,7 @@ struct SpmmLaunch {
   _Float16* xpack;  // workspace area of xpack_bytes(K, N) for X in MFMA fragment order (used when N > 32)
   uint32_t M, K, N;
   uint32_t max_tile_words;
+  uint32_t version;  // format version of the blob (1 or 2)
   int num_cus;
 };
 
@@ -34,6 +35,7 @@ struct CompressLaunch {
   unsigned char* out;  // blob
   uint32_t M, K;
   uint32_t policy;
+  uint32_t version;  // 1: 32-bit words (value, location); 2: 8-bit location distances, three bytes per entry
 };
 
 // Columns are processed in groups, one pass over W per group.  The dense baseline and the sparse

@@ -17,6 +17,8 @@
 // Split-K: the tile sequence (band-major) is cut evenly over all waves of the grid; partial
 // bands are summed in LDS inside a workgroup and through fp32 slots in HBM between workgroups.
 // More than 32 columns: fls_spmm_wide.hip.
+#include <type_traits>
+
 #include "fls_device.h"
 #include "fls_launch.h"
 #include "fls_tile.h"
@@ -42,8 +44,13 @@ struct SpmmParams {
   OutParams out;
 };
 
-template <int NB, int WAVES, int R, int NS>
+// FMT = format version of the blob: 1 = 32-bit words (value, location), R rounds of 256 words staged
+// per tile; 2 = groups of four entries in three words with 8-bit location distances, R rounds of 64
+// groups (256 entries, 192 words) staged per tile.
+template <int NB, int WAVES, int R, int NS, int FMT>
 __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
+  typedef typename std::conditional<FMT == 2, u32x3, u32x4>::type stage_t;  // what a lane loads per round
+  constexpr uint32_t kRoundWords = FMT == 2 ? kRoundWords2 : 256u;
   extern __shared__ __align__(16) unsigned char lds[];
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -92,10 +99,10 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   // buffer descriptor instead: it returns 0 and moves no data.  Nothing is requested past the
   // end of the piece either: the ring runs empty there, so that the hand-over that follows has
   // the registers to itself (no value of the ring is live across it).
-  auto issue = [&](u32x4(&s)[R], u32x4(&x)[NB], uint32_t& begin, uint32_t& end) {
+  auto issue = [&](stage_t(&s)[R], u32x4(&x)[NB], uint32_t& begin, uint32_t& end) {
     win.get(ti, begin, end);
     uint32_t n = end - begin;
-    if (n > R * 256u) n = R * 256u;
+    if (n > R * kRoundWords) n = R * kRoundWords;
     if (ti >= pend) {
       n = 0;
       end = begin;  // nothing to extract either
@@ -104,8 +111,13 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
         __builtin_amdgcn_make_buffer_rsrc((void*)(p.words + begin), 0, (int)(n * 4u), kBufferFlags);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      if (FLS_ABLATE & 32) s[r] = u32x4{(uint32_t)lane, 1u, 2u, 3u};
-      else s[r] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (r * 64 + lane) * 16, 0, kAuxNonTemporal);
+      if constexpr (FMT == 2) {
+        if (FLS_ABLATE & 32) s[r] = u32x3{(uint32_t)lane, 1u, 0x01010101u};
+        else s[r] = __builtin_amdgcn_raw_buffer_load_b96(rsrc, (r * 64 + lane) * 12, 0, kAuxNonTemporal);
+      } else {
+        if (FLS_ABLATE & 32) s[r] = u32x4{(uint32_t)lane, 1u, 2u, 3u};
+        else s[r] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (r * 64 + lane) * 16, 0, kAuxNonTemporal);
+      }
     }
     xf.template load<NB>(x, kti);
     ++ti;
@@ -117,8 +129,24 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   // that step needs.
   typedef __attribute__((address_space(3))) uint16_t* lds_u16_ptr;
   const uint32_t tile_addr = (uint32_t)(uintptr_t)tile;  // LDS addresses are the low 32 bits
-  auto extract = [&](u32x4(&s)[R], uint32_t begin, uint32_t end) {
+  auto extract = [&](stage_t(&s)[R], uint32_t begin, uint32_t end) {
     const uint32_t n = end - begin;
+    if constexpr (FMT == 2) {
+      // locations are running sums of the entries' distances: a lane's group starts where the groups of
+      // the lanes (and rounds) before it end - a wave prefix sum of the groups' distance sums per round
+      uint32_t counter = 0;
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const uint32_t sum = __builtin_amdgcn_sad_u8(s[r][2], 0u, 0u);  // the four distances added up
+        const uint32_t incl = wave_prefix_sum(sum, lane);
+        // no branch: a lane past the end of the run (its loads returned 0) writes zeros to the padding slot
+        const bool mine = (r * 64 + lane) * kGroupWords < n;
+        if (!(FLS_ABLATE & 4)) extract_group(s[r], mine ? counter + incl - sum : 0u, mine ? tile_addr : tile_addr + (uint32_t)kTileBytes);
+        counter += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+      }
+      if (n > R * kRoundWords) extract_overflow_v2(p.words, begin + R * kRoundWords, end, counter, tile);
+      return;
+    } else {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       // no branch: a lane past the end of the run (its loads returned 0: location 0, value 0) gets
@@ -134,15 +162,18 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
       }
     }
     if (n > R * 256u) extract_overflow(p.words, begin + R * 256u, end, tile);
+    }
   };
 
   // rst_smem for sparse tiles: instead of zeroing all 8 KB (eight 16 B stores per lane, 64 LDS
   // clocks), store a zero at the places the tile's words went to - the same count of 2 B stores
   // as the extraction, which is less LDS time as long as a tile has at most about 1000 words.
-  constexpr bool kUnscatter = R <= 4;
-  auto unscatter = [&](const u32x4(&s)[R], uint32_t begin, uint32_t end) {
+  // (version 2 keeps no addresses: its tiles are always cleared whole)
+  constexpr bool kUnscatter = FMT == 1 && R <= 4;
+  auto unscatter = [&](const stage_t(&s)[R], uint32_t begin, uint32_t end) {
     const uint32_t n = end - begin;
-    if (n > R * 256u) {  // the overflow path wrote words this wave no longer holds
+    if constexpr (FMT == 2) {
+    } else if (n > R * 256u) {  // the overflow path wrote words this wave no longer holds
 #pragma unroll
       for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
     } else {
@@ -226,11 +257,11 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   // is straight-line in the ring's loads - every step issues the same number, none under a
   // condition - which lets the compiler wait for exactly the stage it needs
   // (s_waitcnt vmcnt(n), n = loads issued since).
-  u32x4 s[NS][R];
+  stage_t s[NS][R];
   u32x4 x[NS][NB];
   uint32_t sb[NS], se[NS];  // word range of the tile each stage holds
 
-  auto step = [&](u32x4(&ss)[R], u32x4(&sx)[NB], uint32_t& b, uint32_t& e) {
+  auto step = [&](stage_t(&ss)[R], u32x4(&sx)[NB], uint32_t& b, uint32_t& e) {
     // Two waves share a SIMD and, at equal priority, the older one wins every issue slot both
     // want (LDS and memory instructions compete CU-wide), so it would finish its run microseconds
     // ahead of the younger, which then runs the tail alone.  The younger waves sit at priority 1;
@@ -333,29 +364,29 @@ constexpr int ring_depth(int NB, int WAVES, int R) {
   return NB == 1 && R > 4 ? 3 : 2;
 }
 
-template <int NB, int WAVES, int R>
+template <int NB, int WAVES, int R, int FMT>
 static hipError_t launch_variant(const SpmmParams& p, int grid, hipStream_t stream) {
   constexpr int NS = ring_depth(NB, WAVES, R);
   static bool attr_done = false;
   const int lds_bytes = WAVES * wave_lds(NB) + (int)sizeof(WgReduceLds<NB>);
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)spmm_kernel<NB, WAVES, R, NS>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    hipError_t e = hipFuncSetAttribute((const void*)spmm_kernel<NB, WAVES, R, NS, FMT>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        lds_bytes);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL((spmm_kernel<NB, WAVES, R, NS>), dim3(grid), dim3(WAVES * 64), lds_bytes, stream, p);
+  hipLaunchKernelGGL((spmm_kernel<NB, WAVES, R, NS, FMT>), dim3(grid), dim3(WAVES * 64), lds_bytes, stream, p);
   return hipGetLastError();
 }
 
-template <int NB, int WAVES>
+template <int NB, int WAVES, int FMT>
 static hipError_t launch_r(int R, const SpmmParams& p, int grid, hipStream_t stream) {
   switch (R) {
-    case 2: return launch_variant<NB, WAVES, 2>(p, grid, stream);
-    case 3: return launch_variant<NB, WAVES, 3>(p, grid, stream);
-    case 4: return launch_variant<NB, WAVES, 4>(p, grid, stream);
-    case 6: return launch_variant<NB, WAVES, 6>(p, grid, stream);
-    default: return launch_variant<NB, WAVES, 8>(p, grid, stream);
+    case 2: return launch_variant<NB, WAVES, 2, FMT>(p, grid, stream);
+    case 3: return launch_variant<NB, WAVES, 3, FMT>(p, grid, stream);
+    case 4: return launch_variant<NB, WAVES, 4, FMT>(p, grid, stream);
+    case 6: return launch_variant<NB, WAVES, 6, FMT>(p, grid, stream);
+    default: return launch_variant<NB, WAVES, 8, FMT>(p, grid, stream);
   }
 }
 
@@ -375,26 +406,29 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
   const int grid = pick_grid(a.M / kTileM, a.K / kTileK, a.num_cus);
   // rounds of 256 words staged per tile: the smallest variant that holds the densest tile
   // (a denser tile is still handled, through a slow path)
+  const bool v2 = a.version == 2;
+  const uint32_t round_words = v2 ? kRoundWords2 : 256u;
   int R = 8;
-  if (a.max_tile_words <= 2 * 256) R = 2;
-  else if (a.max_tile_words <= 3 * 256) R = 3;
-  else if (a.max_tile_words <= 4 * 256) R = 4;
-  else if (a.max_tile_words <= 6 * 256) R = 6;
+  if (a.max_tile_words <= 2 * round_words) R = 2;
+  else if (a.max_tile_words <= 3 * round_words) R = 3;
+  else if (a.max_tile_words <= 4 * round_words) R = 4;
+  else if (a.max_tile_words <= 6 * round_words) R = 6;
   // The 64-column pass stages at most 2560 words of a tile (it has no slow path for more; twelve
   // rounds of 256 no longer fit its registers): a matrix with denser tiles - less than 40 % sparse
   // somewhere - takes 32-column passes throughout.
-  const bool wide_ok = a.max_tile_words <= 10 * 256;
+  // (and so does a version-2 blob: the 64-column pass reads version 1 only)
+  const bool wide_ok = !v2 && a.max_tile_words <= 10 * 256;
   for (uint32_t n0 = 0; n0 < a.N;) {
     p.out.n0 = n0;
     const uint32_t left = a.N - n0;
     hipError_t e;
     if (left <= 16) {
       p.X = a.X;
-      e = launch_r<1, 8>(R, p, grid, stream);
+      e = v2 ? launch_r<1, 8, 2>(R, p, grid, stream) : launch_r<1, 8, 1>(R, p, grid, stream);
       n0 += 16;
     } else if (left <= 32 || !wide_ok) {
       p.X = a.X;
-      e = launch_r<2, 8>(R, p, grid, stream);
+      e = v2 ? launch_r<2, 8, 2>(R, p, grid, stream) : launch_r<2, 8, 1>(R, p, grid, stream);
       n0 += 32;
     } else {
       e = launch_spmm_wide(a, n0, stream);

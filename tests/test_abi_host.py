@@ -21,7 +21,7 @@ def fls():
 
 def test_every_declared_symbol_is_exported(fls):
     hdr = open(os.path.join(ROOT, "include", "fls.h")).read()
-    declared = set(re.findall(r"\b(fls_[a-z_]+)\s*\(", hdr))
+    declared = set(re.findall(r"\b(fls_[a-z0-9_]+)\s*\(", hdr))
     assert declared == set(fls.EXPORTS)
     L = fls.lib()
     for name in declared:
