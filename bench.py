@@ -37,7 +37,6 @@ OTHERS = ("C2", "C3")   # reported beside it in the same JSON line
 # under profiles/; the line carries the figure together with the file it was copied from, or null.
 MEASURED_TRAFFIC = {
     "C2": (169.94e6, "profiles/spmm_C2_hbm_traffic.md (separate rocprofv3 --pmc runs, not this run)"),
-    "C4": (342.1e6, "profiles/spmm_C4_hbm_traffic.md (separate rocprofv3 --pmc runs, not this run)"),
 }
 
 
@@ -330,7 +329,7 @@ def measure_config(name, args, with_dense, with_cpu):
     t_hbm_us = alg_bytes / (HBM_PEAK_GBS * 1e3)
     t_mfma_us = flops / (MFMA_F16_PEAK_TFLOPS * 1e6)
     narrow = N <= 32 or st["max_tile_words"] > 2560
-    kernels = "fls::spmm_kernel" if narrow else "fls::xpack_kernel + fls::spmm_wide_kernel + fls::wide_reduce_kernel"
+    kernels = "fls::spmm_kernel" if narrow else "fls::spmm_wide_kernel + fls::wide_reduce_kernel"
     traffic = MEASURED_TRAFFIC.get(name)
     res = {
         "name": name, "cfg": cfg, "st": st, "n_copies": n_copies, "ms": ms, "host_ms": host_ms, "tflops": tflops,
@@ -346,6 +345,25 @@ def measure_config(name, args, with_dense, with_cpu):
                      "avg_launch_us": round(ms * 1e3, 3),
                      "roof_us": {"hbm_8TBps": round(t_hbm_us, 2), "mfma_f16_2.5PFLOPs": round(t_mfma_us, 2)}},
     }
+
+    # the same matrix in format version 2 (8-bit location distances, 3 bytes per nonzero), timed the same way and
+    # stated against its own bytes
+    if args.v2:
+        W2 = torch.from_numpy(Wb.view(np.float16)).cuda()
+        b2, st2 = fls.fls_compress_v2(W2)
+        b2 = b2.clone()
+        del W2
+        blobs2 = [b2] + [b2.clone() for _ in range(max(2, -(-MIN_ROTATION_BYTES // st2["bytes_total"])) - 1)]
+        C2 = torch.empty((N, M), dtype=torch.float16, device="cuda")
+        ms2, _ = _time_loop([fls.prepare_spmm(b, X, C2, M, K, N) for b in blobs2], args.steps, args.warmup)
+        alg2 = st2["bytes_total"] + 2 * K * N + 2 * M * N
+        res["format_v2"] = {"blob_bytes": st2["bytes_total"], "bytes_per_nnz": round(st2["bytes_nonzeros"] / max(st2["nnz"], 1), 3),
+                            "ms_per_step": round(ms2, 5), "achieved_GBps_on_its_bytes": round(alg2 / ms2 / 1e6, 1),
+                            "hbm_frac_on_its_bytes": round(alg2 / ms2 / 1e6 / HBM_PEAK_GBS, 4),
+                            "speedup_vs_v1": round(ms / ms2, 3), "_C": C2.cpu().numpy()}
+        for b in blobs2:
+            fls.fls_forget(b)
+        del blobs2, b2, C2
 
     # the empirical ceiling: a plain streaming read of the same blobs (no LDS, no MFMA, nothing stored), with as
     # many workgroups as the kernel uses when it runs one per band, and with one per CU
@@ -406,6 +424,12 @@ def measure_config(name, args, with_dense, with_cpu):
                                          f"skipped, {dt:.3f} s per pass, mean of {reps} passes"}
         res["parity"] = {"max_rel_err_vs_oracle": err, "rows_checked": M, "tolerance": PARITY_TOL,
                          "ok": bool(err <= PARITY_TOL)}
+        if "format_v2" in res:
+            err2 = float(np.abs(res["format_v2"]["_C"].astype(np.float64) - ref).max()) / scale
+            res["format_v2"]["max_rel_err_vs_oracle"] = err2
+            res["parity"]["ok"] = bool(res["parity"]["ok"] and err2 <= PARITY_TOL)
+    if "format_v2" in res:
+        res["format_v2"].pop("_C")
     for b in blobs:
         fls.fls_forget(b)
     return res
@@ -427,6 +451,8 @@ def main():
     ap.add_argument("--no-others", action="store_true",
                     help="leave out the other named configurations (C2, C3) that the default run reports beside the headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-v2", dest="v2", action="store_false",
+                    help="leave out the run of the same matrix in format version 2 (3 bytes per nonzero)")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the bench line: the 12288 x 12288 sweep (sparsity x mask x N, each with its dense pair)")
@@ -476,7 +502,7 @@ def main():
         "host_ms_per_step": round(r["host_ms"], 5),
         "roofline": r["roofline"], "stream_ceiling": r["stream_ceiling"],
     }
-    for key in ("dense_gemm", "vendor_gemm", "cpu_baseline", "parity"):
+    for key in ("format_v2", "dense_gemm", "vendor_gemm", "cpu_baseline", "parity"):
         if key in r:
             out[key] = r[key]
     gen_s = r["t_gen"]
@@ -498,7 +524,7 @@ def main():
             rec = {"workload": _workload_text(o["cfg"], o["st"]), "ms_per_step": round(o["ms"], 5),
                    "TFLOPs": round(o["tflops"], 2), "achieved_GBps": round(o["gbs"], 1), "roofline": o["roofline"],
                    "stream_ceiling": o["stream_ceiling"], "nnz": o["st"]["nnz"], "blob_bytes": o["st"]["bytes_total"]}
-            for key in ("dense_gemm", "vendor_gemm", "parity"):
+            for key in ("format_v2", "dense_gemm", "vendor_gemm", "parity"):
                 if key in o:
                     rec[key] = o[key]
             if "parity" in o and not o["parity"]["ok"]:
