@@ -94,7 +94,9 @@ int fls_compress_bound(int64_t M, int64_t K, size_t* bytes_host);
  *   out_dev      out: blob; caller-owned, out_capacity bytes, 16-byte aligned
  *   order_policy in : FLS_ORDER_LOCATION (FLS_ORDER_BANK blobs are accepted by fls_spmm, but this
  *                     call does not produce them: FLS_EINVAL)
- *   stats_host   out: may be NULL; filled on FLS_OK, and bytes_total also on FLS_ECAPACITY
+ *   stats_host   out: may be NULL; filled on FLS_OK; on FLS_ECAPACITY bytes_total holds a size that is enough
+ *                     (the exact size once the tiles are counted, the worst-case bound if out_capacity
+ *                     did not even hold header and TileOffsets)
  * The result is a pure function of (W bits, M, K, order_policy).  Waits for its own kernels.
  * Uses the start of out_dev as scratch, so out_capacity must cover header and TileOffsets even
  * for an all-zero matrix.  Errors: FLS_EINVAL, FLS_EALIGN, FLS_ECAPACITY, FLS_EHIP.
@@ -178,6 +180,18 @@ int fls_check_workspace(fls_stream_t stream);
  */
 int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int64_t K, int64_t N,
              fls_stream_t stream);
+
+/*
+ * fls_spmm without the library's memory of blob addresses: the blob's statistics come from the caller
+ * (stats_host: as filled by fls_compress, fls_compress_v2 or fls_inspect for this blob; read during
+ * the call only) instead of a header read-back, so the call copies nothing, waits for nothing on
+ * any blob address - first sight included - and keeps no state about the blob.  Otherwise as fls_spmm
+ * (same kernels, same registered workspace, any N up to FLS_MAX_N).  stats_host must describe the
+ * blob at Wc_dev (same M, K, tile geometry): FLS_EFORMAT otherwise; a max_tile_words smaller than the
+ * blob's costs speed only.  Errors: FLS_EINVAL, FLS_EALIGN, FLS_EFORMAT, FLS_EWORKSPACE, FLS_EHIP.
+ */
+int fls_spmm_stats(const void* Wc_dev, const fls_stats* stats_host, const void* X_dev, void* C_dev, int64_t M,
+                   int64_t K, int64_t N, fls_stream_t stream);
 
 /*
  * fls_spmm for callers that cannot allocate device memory or wait on a stream: code under HIP graph

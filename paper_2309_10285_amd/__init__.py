@@ -26,7 +26,7 @@ _lib = None
 _ws_tensor = None  # keeps the registered workspace alive
 
 EXPORTS = ("fls_compress_bound", "fls_compress", "fls_compress_bound_v2", "fls_compress_v2", "fls_inspect", "fls_workspace_bytes", "fls_set_workspace",
-           "fls_check_workspace", "fls_spmm", "fls_spmm_noalloc", "fls_forget", "fls_dense_gemm", "fls_strerror")
+           "fls_check_workspace", "fls_spmm", "fls_spmm_stats", "fls_spmm_noalloc", "fls_forget", "fls_dense_gemm", "fls_strerror")
 
 
 class FlsStats(ctypes.Structure):
@@ -72,6 +72,8 @@ def lib():
         L.fls_check_workspace.restype = ci
         L.fls_spmm.argtypes = [vp, vp, vp, i64, i64, i64, vp]
         L.fls_spmm.restype = ci
+        L.fls_spmm_stats.argtypes = [vp, ctypes.POINTER(FlsStats), vp, vp, i64, i64, i64, vp]
+        L.fls_spmm_stats.restype = ci
         L.fls_spmm_noalloc.argtypes = [vp, ctypes.POINTER(FlsStats), vp, vp, i64, i64, i64, vp]
         L.fls_spmm_noalloc.restype = ci
         L.fls_forget.argtypes = [vp]
@@ -180,6 +182,20 @@ def fls_spmm(blob, X, C, M, K, N):
     assert C.is_cuda and C.dtype == torch.float16 and C.is_contiguous() and tuple(C.shape) == (N, M)
     _check(lib().fls_spmm(ctypes.c_void_p(blob.data_ptr()), ctypes.c_void_p(X.data_ptr()),
                           ctypes.c_void_p(C.data_ptr()), M, K, N, _stream()), "fls_spmm")
+    return C
+
+
+def fls_spmm_stats(blob, stats, X, C, M, K, N):
+    """fls_spmm with the blob's statistics passed in (the dict fls_compress / fls_compress_v2 / fls_inspect returned):
+    no header read-back, nothing remembered about the blob."""
+    import torch
+
+    assert blob.is_cuda and blob.dtype == torch.uint8 and blob.is_contiguous()
+    assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and tuple(X.shape) == (N, K)
+    assert C.is_cuda and C.dtype == torch.float16 and C.is_contiguous() and tuple(C.shape) == (N, M)
+    st = FlsStats(**{k: stats[k] for k, _ in FlsStats._fields_})
+    _check(lib().fls_spmm_stats(ctypes.c_void_p(blob.data_ptr()), ctypes.byref(st), ctypes.c_void_p(X.data_ptr()),
+                                ctypes.c_void_p(C.data_ptr()), M, K, N, _stream()), "fls_spmm_stats")
     return C
 
 

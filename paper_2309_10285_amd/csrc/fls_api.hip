@@ -24,6 +24,7 @@ struct BlobInfo {
 
 std::mutex g_mu;
 std::unordered_map<const void*, BlobInfo> g_blobs;  // blob address -> validated header
+constexpr size_t kMaxRememberedBlobs = 4096;  // beyond this the map is emptied (entries only save a header read-back)
 void* g_ws = nullptr;
 size_t g_ws_bytes = 0;
 int g_num_cus = 0;
@@ -176,7 +177,11 @@ static int compress_impl(const void* W_dev, int64_t M, int64_t K, void* out_dev,
   if (out_capacity < index_bytes) {
     if (stats_host) {
       memset(stats_host, 0, sizeof(*stats_host));
-      stats_host->bytes_total = index_bytes;  // a lower bound: the words are not counted yet
+      // the words are not counted yet: the worst case is a size that is certainly enough
+      size_t bound = 0;
+      if (version == FLS_FORMAT_VERSION_2) fls_compress_bound_v2(M, K, &bound);
+      else fls_compress_bound(M, K, &bound);
+      stats_host->bytes_total = bound;
     }
     return FLS_ECAPACITY;
   }
@@ -208,6 +213,7 @@ static int compress_impl(const void* W_dev, int64_t M, int64_t K, void* out_dev,
   if (stats_host) *stats_host = st;
   {
     std::lock_guard<std::mutex> lk(g_mu);
+    if (g_blobs.size() >= kMaxRememberedBlobs) g_blobs.clear();
     g_blobs[out_dev] = info;
   }
   return FLS_OK;
@@ -313,6 +319,7 @@ int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int6
       g_blobs.erase(Wc_dev);
       return rc;
     }
+    if (g_blobs.size() >= kMaxRememberedBlobs) g_blobs.clear();
     g_blobs[Wc_dev] = info;
   }
   if (info.M != (uint64_t)M || info.K != (uint64_t)K) return FLS_EFORMAT;
@@ -335,6 +342,46 @@ int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int6
   return fls::launch_spmm(a, (hipStream_t)stream) == hipSuccess ? FLS_OK : FLS_EHIP;
 }
 
+// Do the caller's statistics describe a blob of this shape?  (They stand in for the header read-back of fls_spmm.)
+static bool stats_match(const fls_stats* st, int64_t M, int64_t K) {
+  return (st->format_version == FLS_FORMAT_VERSION || st->format_version == FLS_FORMAT_VERSION_2) && st->tile_m == FLS_TILE_M &&
+         st->tile_k == FLS_TILE_K && st->M == (uint64_t)M && st->K == (uint64_t)K && st->num_tiles == num_tiles(M, K) &&
+         st->max_tile_words <= FLS_TILE_M * FLS_TILE_K && st->bytes_offsets == 4 * n_off_of(num_tiles(M, K));
+}
+
+int fls_spmm_stats(const void* Wc_dev, const fls_stats* stats_host, const void* X_dev, void* C_dev, int64_t M, int64_t K,
+                   int64_t N, fls_stream_t stream) {
+  if (!stats_host) return FLS_EINVAL;
+  int rc = check_mm_args(Wc_dev, X_dev, C_dev, M, K, N);
+  if (rc != FLS_OK) return rc;
+  if (!stats_match(stats_host, M, K)) return FLS_EFORMAT;
+  size_t need, xpack_offset;
+  workspace_layout(K, N, &need, &xpack_offset);
+  void* ws;
+  {
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!g_ws || g_ws_bytes < need) return FLS_EWORKSPACE;
+    ws = g_ws;
+  }
+  const int cus = num_cus();
+  if (cus <= 0) return FLS_EHIP;
+  fls::SpmmLaunch a;
+  a.offs = (const uint32_t*)((const unsigned char*)Wc_dev + FLS_HEADER_BYTES);
+  a.words = a.offs + n_off_of(num_tiles(M, K));
+  a.X = (const _Float16*)X_dev;
+  a.C = (_Float16*)C_dev;
+  a.flags = (uint32_t*)ws;
+  a.parts = (float*)((unsigned char*)ws + kCounterAreaBytes);
+  a.xpack = (_Float16*)((unsigned char*)ws + xpack_offset);
+  a.M = (uint32_t)M;
+  a.K = (uint32_t)K;
+  a.N = (uint32_t)N;
+  a.max_tile_words = (uint32_t)stats_host->max_tile_words;
+  a.version = stats_host->format_version;
+  a.num_cus = cus;
+  return fls::launch_spmm(a, (hipStream_t)stream) == hipSuccess ? FLS_OK : FLS_EHIP;
+}
+
 int fls_spmm_noalloc(const void* Wc_dev, const fls_stats* stats_host, const void* X_dev, void* C_dev, int64_t M,
                      int64_t K, int64_t N, fls_stream_t stream) {
   if (!stats_host) return FLS_EINVAL;
@@ -342,10 +389,7 @@ int fls_spmm_noalloc(const void* Wc_dev, const fls_stats* stats_host, const void
   if (rc != FLS_OK) return rc;
   if (N > FLS_NOALLOC_MAX_N) return FLS_ESCRATCH;  // partial sums of wider calls do not fit the static array
   // the caller's stats stand in for the header read-back of fls_spmm: nothing is copied, nothing is waited for
-  if ((stats_host->format_version != FLS_FORMAT_VERSION && stats_host->format_version != FLS_FORMAT_VERSION_2) || stats_host->tile_m != FLS_TILE_M || stats_host->tile_k != FLS_TILE_K ||
-      stats_host->M != (uint64_t)M || stats_host->K != (uint64_t)K || stats_host->num_tiles != num_tiles(M, K) ||
-      stats_host->max_tile_words > FLS_TILE_M * FLS_TILE_K || stats_host->bytes_offsets != 4 * n_off_of(num_tiles(M, K)))
-    return FLS_EFORMAT;
+  if (!stats_match(stats_host, M, K)) return FLS_EFORMAT;
   unsigned char* ptr = scratch_on_current_device(&rc);
   if (!ptr) return rc;
   const int cus = num_cus();

@@ -159,16 +159,21 @@ static hipError_t launch_dense_variant(const DenseParams& p, int grid, hipStream
 // LDS, no barrier, no waiting between workgroups.  A step covers 128 rows x 64 k: lane l reads 32
 // contiguous bytes of its row, so four lanes read a whole 128 B line, and the two MFMA K-steps of
 // a step take the first and the second 16 B; X follows the same assignment of k to lanes.
-#ifndef FLS_DENSE_WIDE_NS
-#define FLS_DENSE_WIDE_NS 2
-#endif
+constexpr int kDenseWideRing = 2;  // steps of 128 x 64 in flight per wave
 
 template <int NS>
 __global__ __launch_bounds__(256) void dense_wide_kernel(WideParams p) {
   constexpr int NB = 4;
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const uint32_t group = blockIdx.x / p.S, slice = blockIdx.x - group * p.S;
+  // (group of four bands, K slice) pair and group of 64 columns of this workgroup: as in the sparse
+  // pass, the G workgroups that stream the same rows of W get ids 8 apart, which puts them on one
+  // XCD one after the other, so that all but the first find W in its L2
+  const uint32_t pairs = ((p.bands + 3u) / 4u) * p.S;
+  const uint32_t cg = (blockIdx.x >> 3) % p.G, pair = ((blockIdx.x >> 3) / p.G) * 8u + (blockIdx.x & 7u);
+  if (pair >= pairs) return;
+  const uint32_t group = pair / p.S, slice = pair - group * p.S;
+  const uint32_t n0 = p.n0 + cg * 64u;
   const uint32_t band = group * 4 + wave;
   if (band >= p.bands) return;
   const uint32_t K = p.K, KT = p.KT;  // KT: steps of 64 k per band (the last one may be half)
@@ -187,8 +192,8 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(WideParams p) {
   const uint32_t ktiles = K / kTileK, xblocks = (p.N + 15u) / 16u;
   const __amdgpu_buffer_rsrc_t xrsrc =
       __builtin_amdgcn_make_buffer_rsrc((void*)p.Xp, 0, (int)(ktiles * xblocks * 1024u), kBufferFlags);
-  const uint32_t xlane = (p.n0 / 16u) * 1024u + ((2u * (g & 1u)) * 16u + c) * 16u;
-  const uint32_t xvalid = xblocks - p.n0 / 16u;  // column blocks left from n0 on: the others read as zero
+  const uint32_t xlane = (n0 / 16u) * 1024u + ((2u * (g & 1u)) * 16u + c) * 16u;
+  const uint32_t xvalid = n0 / 16u < xblocks ? xblocks - n0 / 16u : 0u;  // column blocks left from n0 on: the others read as zero
   // a half last step (K = 64 j + 32): the lanes of its upper 32 k drop out
   const bool half_last = (K & 63u) != 0;
   const bool upper = g >= 2;
@@ -254,10 +259,10 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(WideParams p) {
     o.C = p.C;
     o.M = p.M;
     o.N = p.N;
-    o.n0 = p.n0;
+    o.n0 = n0;
     store_band<NB>(o, acc, band, lane);
   } else {
-    float4v* dst = (float4v*)p.parts + ((size_t)(band * p.S + slice) * (NB * kRowBlocks)) * 64 + lane;
+    float4v* dst = (float4v*)p.parts + ((size_t)((band * p.G + cg) * p.S + slice) * (NB * kRowBlocks)) * 64 + lane;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -265,12 +270,14 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(WideParams p) {
   }
 }
 
-static hipError_t launch_dense_wide(const DenseLaunch& a, uint32_t n0, hipStream_t stream) {
+// `col_groups` groups of 64 columns from column n0 on, in one launch (the last group may reach past N)
+static hipError_t launch_dense_wide(const DenseLaunch& a, uint32_t n0, uint32_t col_groups, hipStream_t stream) {
   WideParams p;
   p.offs = nullptr;
   p.words = nullptr;
   p.W = a.W;
   p.X = nullptr;
+  p.G = col_groups;
   p.Xp = a.xpack;
   p.C = a.C;
   p.parts = a.parts;
@@ -280,9 +287,10 @@ static hipError_t launch_dense_wide(const DenseLaunch& a, uint32_t n0, hipStream
   p.n0 = n0;
   p.KT = (a.K + 63u) / 64u;
   p.bands = a.M / kTileM;
-  p.S = wide_slices(p.bands, p.KT, a.num_cus);
+  p.S = wide_slices(p.bands, col_groups, p.KT, a.num_cus);
   const uint32_t groups = (p.bands + 3u) / 4u;
-  hipLaunchKernelGGL((dense_wide_kernel<FLS_DENSE_WIDE_NS>), dim3(groups * p.S), dim3(256), 0, stream, p);
+  const uint32_t grid = (groups * p.S + 7u) / 8u * 8u * col_groups;
+  hipLaunchKernelGGL((dense_wide_kernel<kDenseWideRing>), dim3(grid), dim3(256), 0, stream, p);
   hipError_t e = hipGetLastError();
   if (e == hipSuccess && p.S > 1) e = launch_wide_reduce(p, false, stream);
   return e;
@@ -308,8 +316,9 @@ hipError_t launch_dense(const DenseLaunch& a, hipStream_t stream) {
     const uint32_t left = a.N - n0;
     hipError_t e;
     if (left > kGroupCols) {
-      e = launch_dense_wide(a, n0, stream);
-      n0 += kSpmmGroupCols;
+      const uint32_t col_groups = left / kSpmmGroupCols + (left % kSpmmGroupCols > kGroupCols ? 1u : 0u);
+      e = launch_dense_wide(a, n0, col_groups, stream);
+      n0 += col_groups * kSpmmGroupCols;
     } else {
       const uint32_t h = left <= 16 ? 2 : 1;
       p.out.KT = (a.K + 32 * h - 1) / (32 * h);

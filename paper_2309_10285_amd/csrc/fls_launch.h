@@ -50,20 +50,22 @@ constexpr uint32_t kMaxWorkgroups = 512;    // must equal fls::kMaxGrid of the d
 // per band, and keeps one 128 x 64 fp32 partial result per band and slice.  Slices per group: as
 // many as fill the CUs, but none shorter than 16 steps.  groups * slices <= kMaxWorkgroups, so
 // bands * slices <= 4 * kMaxWorkgroups partial results at most (what parts_floats provides).
-inline uint32_t wide_slices(uint32_t bands, uint32_t KT, int cus) {
+inline uint32_t wide_slices(uint32_t bands, uint32_t col_groups, uint32_t KT, int cus) {
   if (cus > (int)kMaxWorkgroups) cus = (int)kMaxWorkgroups;
-  const uint32_t groups = (bands + 3) / 4;
-  uint32_t S = groups < (uint32_t)cus ? (uint32_t)cus / groups : 1u;
+  const uint64_t units = (uint64_t)((bands + 3) / 4) * col_groups;  // (group of four bands, group of 64 columns)
+  uint32_t S = units < (uint64_t)cus ? (uint32_t)((uint64_t)cus / units) : 1u;
   const uint32_t by_length = KT / 16u > 0 ? KT / 16u : 1u;
   return S < by_length ? S : by_length;
 }
-// The sparse 64-column pass: a workgroup takes four bands (one per wave) and a K slice made of whole
-// loop bodies of `body` tiles, and writes one partial result per band and slice.  Slices per group
-// of four bands: as many as fill the CUs, none shorter than two bodies.
-inline uint32_t wide_quad_slices(uint32_t bands, uint32_t KT, int cus, uint32_t body) {
+// The sparse 64-column pass: a workgroup takes four bands (one per wave), a group of 64 columns and a
+// K slice made of whole loop bodies of `body` tiles, and writes one partial result per band, column
+// group and slice.  Slices per (group of four bands, column group): as many as fill the CUs, none
+// shorter than two bodies.  With S > 1, groups of bands x column groups x S <= CUs <= kMaxWorkgroups,
+// so at most 4 * kMaxWorkgroups partial results exist (what parts_floats provides).
+inline uint32_t wide_quad_slices(uint32_t bands, uint32_t col_groups, uint32_t KT, int cus, uint32_t body) {
   if (cus > (int)kMaxWorkgroups) cus = (int)kMaxWorkgroups;
-  const uint32_t quads = (bands + 3) / 4;
-  uint32_t S = quads < (uint32_t)cus ? (uint32_t)cus / quads : 1u;
+  const uint64_t units = (uint64_t)((bands + 3) / 4) * col_groups;
+  uint32_t S = units < (uint64_t)cus ? (uint32_t)((uint64_t)cus / units) : 1u;
   const uint32_t by_length = KT / (2u * body) > 0 ? KT / (2u * body) : 1u;
   return S < by_length ? S : by_length;
 }
@@ -117,12 +119,14 @@ struct WideParams {
   _Float16* C;
   float* parts;           // [band][slice][column block][row block][lane] float4, used when S > 1
   uint32_t M, K, N, n0, KT, bands, S;
+  uint32_t G;  // groups of 64 columns in the launch, from column n0 on (sparse pass; 1 in the dense pass)
 };
 
 hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream);
-// X -> xpack (fragment order, all N columns), then one 64-column pass per call of launch_spmm_wide from column n0 on
+// X -> xpack (fragment order, all N columns): the dense 64-column passes read it
+// `groups` groups of 64 columns of the sparse 64-column pass from column n0 on, in one launch
 hipError_t launch_xpack(const _Float16* X, _Float16* xpack, uint32_t K, uint32_t N, hipStream_t stream);
-hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, hipStream_t stream);
+hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, uint32_t groups, hipStream_t stream);
 // C = sum over the S slices of parts, in slice order (the second kernel of a 64-column pass with S > 1);
 // layout32: the partial results are in the 32x32 accumulator layout (sparse pass), else 16x16 (dense pass)
 hipError_t launch_wide_reduce(const WideParams& p, bool layout32, hipStream_t stream);

@@ -358,9 +358,6 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 // four tiles: 33.7 / 35.5 / 35.8 us; 28672 x 7168 at 90 %, 32 columns, two / four: 30.3 / 31.3 us).
 // A stage costs 4 R + 4 NB registers, the accumulators 32 NB, and a wave has 256 registers.
 constexpr int ring_depth(int NB, int WAVES, int R) {
-#ifdef FLS_NSTAGE
-  if (NB == 1) return FLS_NSTAGE;
-#endif
   return NB == 1 && R > 4 ? 3 : 2;
 }
 
@@ -431,8 +428,10 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
       e = v2 ? launch_r<2, 8, 2>(R, p, grid, stream) : launch_r<2, 8, 1>(R, p, grid, stream);
       n0 += 32;
     } else {
-      e = launch_spmm_wide(a, n0, stream);
-      n0 += kSpmmGroupCols;
+      // all the groups of 64 columns in one launch; a rest of up to 32 columns is left to the narrower passes
+      const uint32_t groups = left / kSpmmGroupCols + (left % kSpmmGroupCols > kGroupCols ? 1u : 0u);
+      e = launch_spmm_wide(a, n0, groups, stream);
+      n0 += groups * kSpmmGroupCols;
     }
     if (e != hipSuccess) return e;
   }

@@ -13,7 +13,7 @@
 //
 // Work is cut as (group of four bands) x (K slice), S slices per group so that the grid fills the
 // CUs.  With S = 1 a wave's sum is its band's result and goes to C directly, otherwise to a
-// partial-sum area [band][slice] that a second, small kernel adds up in slice order and converts
+// partial-sum area [band][column group][slice] that a second, small kernel adds up in slice order and converts
 // (no flags, no waiting between workgroups, deterministic).
 //
 // Inside a wave the stages are those of the narrow kernel - register ring of tiles, extraction by
@@ -125,8 +125,17 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   extern __shared__ __align__(16) unsigned char lds[];
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  // the workgroup: four row bands (one per wave) x one K slice, which all four waves walk together
-  const uint32_t quad = blockIdx.x / p.S, slice = blockIdx.x - quad * p.S;
+  // The workgroup: four row bands (one per wave) x one K slice, which all four waves walk together,
+  // x one group of 64 columns.  A call of more than 64 columns is one launch over all its column
+  // groups (with G groups the chip is filled by G times fewer K slices, so G times fewer partial
+  // sums per column go through memory than with a launch per group).  The G workgroups that stream
+  // the same words get workgroup ids 8 apart: consecutive ids go to the chip's eight XCDs in turn,
+  // so those G land on one XCD, one after the other, and all but the first find the words in its L2.
+  const uint32_t pairs = ((p.bands + 3u) / 4u) * p.S;  // (group of bands, slice) pairs
+  const uint32_t cg = (blockIdx.x >> 3) % p.G, pair = ((blockIdx.x >> 3) / p.G) * 8u + (blockIdx.x & 7u);
+  if (pair >= pairs) return;  // the grid is rounded up to a multiple of eight pairs
+  const uint32_t quad = pair / p.S, slice = pair - quad * p.S;
+  const uint32_t n0 = p.n0 + cg * 64u;
   const uint32_t band = quad * 4 + wave;
   const bool active = band < p.bands;  // a wave past the last band loads no words but shares the X work
   const uint32_t KT = p.KT, T = p.bands * KT;
@@ -171,7 +180,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   // offsets below) and e only adds to the group.  Everything that may leave the buffer - the column and,
   // for the chunk requested past the end of K, the k offset - is in the per-lane offset.
   const uint32_t pair_w = (wave * NS) >> 3, grp_w = (wave * NS) & 7u;
-  const uint32_t xg_lane = ((p.n0 + 8u * grp_w + c8) * p.K + pair_w * 64u + ch * 8u) * 2u;  // + e column groups + the chunk's k
+  const uint32_t xg_lane = ((n0 + 8u * grp_w + c8) * p.K + pair_w * 64u + ch * 8u) * 2u;  // + e column groups + the chunk's k
   // LDS byte address of this lane's store of load e, by e & 3 (the column group inside its 32-column
   // block), in the chunk to fill: k chunk ch of the tile pair = tile parity ch >> 2, step (ch >> 1) & 1,
   // lane half ch & 1
@@ -354,7 +363,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
 
   // B fragments straight from the caller's X, for the plain loop: lane 32 h + c takes column c of a
   // 32-column block, k chunk h of a 16-k step
-  const uint32_t xd_lane = ((p.n0 + ((uint32_t)lane & 31u)) * p.K + ((uint32_t)lane >> 5) * 8u) * 2u;
+  const uint32_t xd_lane = ((n0 + ((uint32_t)lane & 31u)) * p.K + ((uint32_t)lane >> 5) * 8u) * 2u;
   // One tile the plain way: words straight from memory into LDS, fragments, re-zero, MFMAs.
   auto plain_tile = [&](uint32_t t, uint32_t kt) {
     const uint32_t begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)offs[t]);
@@ -439,10 +448,10 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   // The band's result for the slice: to C directly when the slice is all of K, else to the
   // partial-sum area [band][slice] that a second, small kernel adds up in slice order.
   if (p.S == 1) {
-    store_band32(p.C, p.M, p.N, p.n0, acc, band, lane);
+    store_band32(p.C, p.M, p.N, n0, acc, band, lane);
   } else {
-    // [band][slice][column block][row block][q][lane] float4: rows 8 q + 4 (lane >> 5) + (0..3) of the row block
-    float4v* dst = (float4v*)p.parts + ((size_t)(band * p.S + slice) * (NB * kRowBlocks)) * 64 + lane;
+    // [band][column group][slice][column block][row block][q][lane] float4: rows 8 q + 4 (lane >> 5) + (0..3) of the row block
+    float4v* dst = (float4v*)p.parts + ((size_t)((band * p.G + cg) * p.S + slice) * (NB * kRowBlocks)) * 64 + lane;
 #pragma unroll
     for (int cb = 0; cb < kColBlocks32; ++cb)
 #pragma unroll
@@ -461,10 +470,11 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
 template <bool LAYOUT32>
 __global__ __launch_bounds__(256) void wide_reduce_kernel(WideParams p) {
   const uint32_t unit = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (unit >= p.bands * (kWideNB * kRowBlocks)) return;
+  if (unit >= p.bands * p.G * (kWideNB * kRowBlocks)) return;
   const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t band = unit / (kWideNB * kRowBlocks), sub = unit - band * (kWideNB * kRowBlocks);
-  const float4v* src = (const float4v*)p.parts + ((size_t)band * p.S * (kWideNB * kRowBlocks) + sub) * 64 + lane;
+  const uint32_t bg = unit / (kWideNB * kRowBlocks), sub = unit - bg * (kWideNB * kRowBlocks);  // (band, column group), block
+  const uint32_t band = bg / p.G, n0 = p.n0 + (bg - band * p.G) * 64u;
+  const float4v* src = (const float4v*)p.parts + ((size_t)bg * p.S * (kWideNB * kRowBlocks) + sub) * 64 + lane;
   float4v sum = {0.f, 0.f, 0.f, 0.f};
   for (uint32_t s0 = 0; s0 < p.S; s0 += 8) {
     float4v v[8];
@@ -479,10 +489,10 @@ __global__ __launch_bounds__(256) void wide_reduce_kernel(WideParams p) {
   }
   uint32_t n, row;
   if (LAYOUT32) {
-    n = p.n0 + (sub / 16u) * 32u + (lane & 31u);
+    n = n0 + (sub / 16u) * 32u + (lane & 31u);
     row = ((sub / 4u) % 4u) * 32u + (sub % 4u) * 8u + (lane >> 5) * 4u;
   } else {
-    n = p.n0 + (sub / kRowBlocks) * 16u + (lane & 15u);
+    n = n0 + (sub / kRowBlocks) * 16u + (lane & 15u);
     row = (sub % kRowBlocks) * 16u + (lane >> 4) * 4u;
   }
   if (n < p.N) {
@@ -503,8 +513,9 @@ static hipError_t launch_wide_variant(WideParams p, int cus, hipStream_t stream)
     attr_done = true;
   }
   const uint32_t quads = (p.bands + 3u) / 4u;
-  p.S = wide_quad_slices(p.bands, p.KT, cus, NS);
-  hipLaunchKernelGGL((spmm_wide_kernel<R, NS>), dim3(quads * p.S), dim3(kWideWaves * 64), kLds, stream, p);
+  p.S = wide_quad_slices(p.bands, p.G, p.KT, cus, NS);
+  const uint32_t grid = (quads * p.S + 7u) / 8u * 8u * p.G;  // (group of bands, slice) pairs rounded up to eight, x column groups
+  hipLaunchKernelGGL((spmm_wide_kernel<R, NS>), dim3(grid), dim3(kWideWaves * 64), kLds, stream, p);
   hipError_t e = hipGetLastError();
   if (e == hipSuccess && p.S > 1) e = launch_wide_reduce(p, true, stream);
   return e;
@@ -518,14 +529,14 @@ hipError_t launch_xpack(const _Float16* X, _Float16* xpack, uint32_t K, uint32_t
 }
 
 hipError_t launch_wide_reduce(const WideParams& p, bool layout32, hipStream_t stream) {
-  const uint32_t units = p.bands * (kWideNB * kRowBlocks);
+  const uint32_t units = p.bands * p.G * (kWideNB * kRowBlocks);
   if (layout32) hipLaunchKernelGGL(wide_reduce_kernel<true>, dim3((units + 3) / 4), dim3(256), 0, stream, p);
   else hipLaunchKernelGGL(wide_reduce_kernel<false>, dim3((units + 3) / 4), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 
-// One 64-column pass starting at column n0.
-hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, hipStream_t stream) {
+// `groups` groups of 64 columns starting at column n0, in one launch (the last group may reach past N).
+hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, uint32_t groups, hipStream_t stream) {
   WideParams p;
   p.offs = a.offs;
   p.words = a.words;
@@ -538,6 +549,7 @@ hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, hipStream_t stream
   p.K = a.K;
   p.N = a.N;
   p.n0 = n0;
+  p.G = groups;
   p.KT = a.K / kTileK;
   p.bands = a.M / kTileM;
   p.S = 1;

@@ -475,3 +475,43 @@ def test_split_bands_after_wide_passes_many_repeats(fls, oracle_mod):
     assert float(worst) / scale <= TOL
     fls.fls_check_workspace()
     fls.fls_forget(blob)
+
+
+@pytest.mark.parametrize("N", [16, 100])
+def test_spmm_with_caller_passed_stats_is_recordable_at_first_sight(fls, oracle_mod, N):
+    """fls_spmm_stats takes the blob's statistics from the caller: no header read-back, nothing remembered.  A
+    call on a blob address the library has never seen can therefore be recorded straight into a HIP graph
+    (fls_spmm would have to copy the header back and wait); every replay must match the oracle."""
+    import torch
+
+    W = CASES[4][1]  # 1536 x 2048: bands cut between workgroups
+    M, K = W.shape
+    blob0, stats = fls.fls_compress(_dev_w(W))
+    blob = blob0.clone()  # an address the library knows nothing about
+    fls.fls_forget()
+    fls.ensure_workspace(M, K, N)
+    X = wl.gen_x(N, K, 880 + N)
+    Xd = torch.from_numpy(X.view(np.float16)).cuda()
+    C = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+    # eager first (sets kernel attributes), on yet another unseen address
+    fls.fls_spmm_stats(blob0.clone(), stats, Xd, C, M, K, N)
+    torch.cuda.synchronize()
+    ref = oracle_mod.ref_spmm_f64(W, X)
+    assert _rel_err(C.cpu().numpy(), ref) <= TOL
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fls.fls_spmm_stats(blob, stats, Xd, C, M, K, N)
+    for rep in range(3):
+        X = wl.gen_x(N, K, 890 + 3 * rep + N)
+        Xd.copy_(torch.from_numpy(X.view(np.float16)))
+        C.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert _rel_err(C.cpu().numpy(), oracle_mod.ref_spmm_f64(W, X)) <= TOL, rep
+    # statistics of another shape are refused on the host
+    bad = dict(stats)
+    bad["K"] = K + 32
+    with pytest.raises(fls.FlsError) as e:
+        fls.fls_spmm_stats(blob, bad, Xd, C, M, K, N)
+    assert e.value.code == fls.EFORMAT
+    fls.fls_check_workspace()
