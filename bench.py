@@ -37,6 +37,7 @@ OTHERS = ("C2", "C3")   # reported beside it in the same JSON line
 # under profiles/; the line carries the figure together with the file it was copied from, or null.
 MEASURED_TRAFFIC = {
     "C2": (169.94e6, "profiles/spmm_C2_hbm_traffic.md (separate rocprofv3 --pmc runs, not this run)"),
+    "C4": (336.31e6, "profiles/spmm_C4_hbm_traffic.md (separate rocprofv3 --pmc runs, not this run; both kernels of the call)"),
 }
 
 
