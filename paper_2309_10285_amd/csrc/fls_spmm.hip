@@ -323,6 +323,34 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     }
   };
 
+  // When the share is exactly one whole band (the band-aligned grid: no partial sum leaves the
+  // workgroup) every wave has one piece of it, and the last thing the whole chip waits for is this
+  // sum.  All waves then meet at a barrier (none has anything else left to do) and share the work:
+  // every wave leaves its accumulators of one column block in its tile buffer, and wave w adds the
+  // eight buffers' row block w in wave order - a fixed order - converts and stores those 16 rows of C.
+  const bool whole_band = share0 % KT == 0 && share1 - share0 == KT && KT >= (uint32_t)WAVES;
+  auto whole_band_sum = [&](uint32_t band) {
+    static_assert(WAVES == kRowBlocks, "one row block per wave");
+    const uint32_t col = lane & 15, rsub = (lane >> 4) * 4;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      if (nb > 0) __syncthreads();  // every wave is done reading the buffers of the column block before
+#pragma unroll
+      for (int rb = 0; rb < kRowBlocks; ++rb) *(float4v*)(tile + rb * 1024 + lane * 16) = acc[rb][nb];
+      __syncthreads();
+      float4v sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w) sum += *(const float4v*)(lds + w * kWaveLds + wave * 1024 + lane * 16);
+      const uint32_t n = p.out.n0 + nb * 16 + col;
+      if (n < p.out.N) {
+        half4 h;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) h[r] = (_Float16)sum[r];
+        *(half4*)(p.out.C + (size_t)n * p.out.M + band * kTileM + wave * 16 + rsub) = h;
+      }
+    }
+  };
+
   if (WAVES > 4 && wave >= WAVES / 2) __builtin_amdgcn_s_setprio(1);
   while (tc < t1) {
     const uint32_t piece0 = tc;
@@ -338,7 +366,8 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 #pragma unroll
     for (int i = 0; i < NS - 1; ++i)
       if (tc < pend) step(s[i], x[i], sb[i], se[i]);
-    if (one_band) one_band_sum(bandc);
+    if (whole_band) whole_band_sum(bandc);
+    else if (one_band) one_band_sum(bandc);
     else hand_over(bandc, pend - piece0);
     ktc += pend - piece0;
     if (ktc == KT) {
