@@ -230,24 +230,31 @@ template <int NB>
 __device__ __forceinline__ void owner_finish(const OutParams& o, float4v (&acc)[kRowBlocks][NB], uint32_t band,
                                              uint32_t wg, uint32_t P, int lane) {
   const uint32_t band_hi = (band + 1) * o.KT;
-  for (uint32_t q = wg + 1; q < P && share_begin(q, o.T, P) < band_hi; ++q) {
-    if (share_begin(q + 1, o.T, P) == share_begin(q, o.T, P)) continue;  // empty share: no contribution
+  // The flags of all contributors are polled at once, one per lane: a look at a flag is a trip to
+  // memory (it lives behind another XCD's L2), and one after the other those trips would add up at the
+  // very end of the kernel.
+  for (uint32_t base = wg + 1; base < P && share_begin(base, o.T, P) < band_hi; base += 64) {
+    const uint32_t q = base + (uint32_t)lane;
+    // workgroup q holds tiles of the band (an empty share contributes nothing)
+    const bool mine = q < P && share_begin(q, o.T, P) < band_hi && share_begin(q + 1, o.T, P) != share_begin(q, o.T, P);
     uint32_t spins = 0;
-    bool seen = true;
-    while (__hip_atomic_load(o.flags + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+    bool seen = !mine;
+    for (;;) {
+      if (!seen) seen = __hip_atomic_load(o.flags + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
+      if (__builtin_amdgcn_ballot_w64(!seen) == 0) break;
       __builtin_amdgcn_s_sleep(8);
       if (++spins == kSpinLimit) {  // never seen; gives up rather than hang, and says so
         if (lane == 0) __hip_atomic_store(o.flags + kMaxGrid, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        seen = false;
         break;
       }
     }
     // workgroup q raises its flag once per launch and nobody else looks at it: down again for the next launch
-    if (seen && lane == 0) __hip_atomic_store(o.flags + q, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (mine && seen) __hip_atomic_store(o.flags + q, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
-  // the acquire that pairs with the contributors' release: nothing this XCD's caches still hold of
-  // the slots may serve the loads below
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+  // What pairs with the contributors' release: the loads below are issued after the flags have been
+  // seen, and each carries sc1 like the look at a flag does - a load at device scope, which nothing
+  // that this CU's L1 or this XCD's L2 still holds of the slots may serve.  (An acquire fence here
+  // would invalidate both caches wholesale on top of that: a microsecond at the very end of the kernel.)
   // As many loads as the registers allow are issued before the first is used: each is a trip
   // to memory, and this runs when the kernel is about to end, with nothing left to hide it behind.
   constexpr int kBatch = NB == 1 ? 4 : 2;  // slots in flight

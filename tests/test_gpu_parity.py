@@ -477,6 +477,44 @@ def test_split_bands_after_wide_passes_many_repeats(fls, oracle_mod):
     fls.fls_forget(blob)
 
 
+@pytest.mark.parametrize("M,K,N", [(7168, 4096, 16), (12288, 6144, 32)])
+def test_two_matrices_taking_turns_on_the_same_partial_sum_slots(fls, oracle_mod, M, K, N):
+    """Two different matrices of one shape, multiplied in turns: both calls use the same grid, so workgroup q of
+    either stores its partial sum at the same address and the band's owner reads it from there (56 bands cut
+    evenly over 224 workgroups; 96 bands cut wherever the shares fall).  An owner that was served a slot's
+    contents of the call before - from a cache on its side - would return the other matrix's band.  First
+    results against the oracle over the whole of C, then 1000 more calls of each."""
+    import torch
+
+    items = []
+    for i in range(2):
+        W = wl.prune_uniform(wl.gen_weights_f32(M, K, 1300 + i), 0.8, 1310 + i)
+        X = wl.gen_x(N, K, 1320 + i)
+        blob, _ = fls.fls_compress(_dev_w(W))
+        items.append(dict(W=W, X=X, blob=blob.clone(), Xd=torch.from_numpy(X.view(np.float16)).cuda()))
+    fls.ensure_workspace(M, K, N)
+    for it in items:
+        C = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+        fls.fls_spmm(it["blob"], it["Xd"], C, M, K, N)
+        torch.cuda.synchronize()
+        got = C.cpu().numpy()
+        assert not np.isnan(got).any()
+        ref = oracle_mod.ref_spmm_f64(it["W"], it["X"])
+        assert float(np.abs(got.astype(np.float64) - ref).max()) / float(np.abs(ref).max()) <= TOL
+        it["first"] = C.float()
+        it["scale"] = float(C.float().abs().max())
+    worst = torch.zeros((), device="cuda")
+    C = torch.empty((N, M), dtype=torch.float16, device="cuda")
+    for rep in range(2000):
+        it = items[rep & 1]
+        C.fill_(float("nan"))
+        fls.fls_spmm(it["blob"], it["Xd"], C, M, K, N)
+        worst = torch.maximum(worst, torch.nan_to_num((C.float() - it["first"]).abs(), nan=float("inf")).max() / it["scale"])
+    assert float(worst) <= TOL
+    fls.fls_check_workspace()
+    fls.fls_forget()
+
+
 @pytest.mark.parametrize("N", [16, 100])
 def test_spmm_with_caller_passed_stats_is_recordable_at_first_sight(fls, oracle_mod, N):
     """fls_spmm_stats takes the blob's statistics from the caller: no header read-back, nothing remembered.  A
