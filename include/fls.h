@@ -176,6 +176,11 @@ int fls_check_workspace(fls_stream_t stream);
  * Stream capture: a call on a blob address the library already knows enqueues kernels only (no
  * copies, no memsets, no host-side per-launch state in their arguments), so it may be recorded
  * into a HIP graph and replayed; make one ordinary call on that address and shape first.
+ * Only the 64-byte header is validated; TileOffsets and NonZeros are the caller's responsibility (a blob
+ * from fls_compress is right by construction).  As a guard for blobs that were stored and read back, the
+ * passes of up to 32 columns take no offset to lie beyond the header's word count, so a truncated or
+ * damaged TileOffsets section gives wrong results, not loads outside NonZeros; the 64-column pass
+ * (N > 32, format version 1) trusts TileOffsets.
  * Errors: FLS_EINVAL, FLS_EALIGN, FLS_EFORMAT, FLS_EWORKSPACE, FLS_EHIP.
  */
 int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int64_t K, int64_t N,

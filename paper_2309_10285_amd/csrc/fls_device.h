@@ -19,6 +19,7 @@ constexpr int kRowBlocks = kTileM / 16;     // 16-row MFMA blocks per tile
 
 constexpr int kHeaderWords = 16;            // the blob's 64-byte header, in 32-bit words; TileOffsets follow it
 constexpr int kHeaderMaxTileWords = 6;      // header word that holds the length of the longest tile
+constexpr int kHeaderTotalWords = 14;       // header word that holds the number of words in NonZeros (low half of a u64)
 
 constexpr int kAccPerBlock = kTileM * 16;   // fp32 values of one 128 x 16 column block
 constexpr int kMaxGrid = 512;               // workgroups a launch may use (sizes the workspace)

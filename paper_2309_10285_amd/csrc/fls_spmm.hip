@@ -63,6 +63,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   OffsetWindow win;
   win.offs = p.offs;
   win.T = T;
+  win.total = p.offs[kHeaderTotalWords - kHeaderWords];  // from the blob's own header, like every length
   win.lane = lane;
   win.request(t0 < T ? t0 : T);
   WgReduceLds<NB>* red = (WgReduceLds<NB>*)(lds + WAVES * kWaveLds);

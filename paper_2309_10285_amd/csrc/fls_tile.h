@@ -11,6 +11,7 @@ namespace fls {
 struct OffsetWindow {
   const uint32_t* offs;
   uint32_t T;       // index of the last entry that differs from its successor (offs[T] = total words)
+  uint32_t total;   // words in NonZeros: no offset is taken to lie beyond (a damaged blob must not send loads elsewhere)
   uint32_t base;    // tile whose offset lane 0 holds
   uint32_t window;  // this lane's offset
   int lane;
@@ -19,7 +20,8 @@ struct OffsetWindow {
   __device__ __forceinline__ void request(uint32_t t) {
     base = t;
     const uint32_t idx = t + (uint32_t)lane;
-    window = offs[idx < T ? idx : T];
+    const uint32_t v = offs[idx < T ? idx : T];
+    window = v < total ? v : total;
   }
   __device__ __forceinline__ void arrive() {
     // Wait for the value here, inside the (rare) reload path: if its arrival were first needed
@@ -37,6 +39,7 @@ struct OffsetWindow {
     if (t - base > 62u) load(t);
     begin = (uint32_t)__builtin_amdgcn_readlane((int)window, (int)(t - base));
     end = (uint32_t)__builtin_amdgcn_readlane((int)window, (int)(t + 1 - base));
+    if (end < begin) end = begin;  // offsets that do not ascend: an empty run
   }
 };
 

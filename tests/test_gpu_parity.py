@@ -477,6 +477,46 @@ def test_split_bands_after_wide_passes_many_repeats(fls, oracle_mod):
     fls.fls_forget(blob)
 
 
+@pytest.mark.parametrize("N", [16, 32])
+def test_offsets_past_the_end_of_nonzeros_are_clamped(fls, oracle_mod, N):
+    """A blob whose last TileOffsets entries point past the end of NonZeros (a truncated or damaged file).  The
+    passes of up to 32 columns take no offset to lie beyond the word count in the blob's header, so the last tile
+    keeps its own words and the result is that of the intact blob.  (The 64-column pass trusts TileOffsets: a
+    clamp there cost 5 - 14 % of its time.)  The buffer has room behind the blob, filled with words (1.0 at
+    location 0) that would change C if they were read: every load of this test stays inside it."""
+    import torch
+
+    M, K = 512, 2048
+    W = wl.prune_uniform(wl.gen_weights_f32(M, K, 1400), 0.8, 1401)
+    X = wl.gen_x(N, K, 1402)
+    blob, st = fls.fls_compress(_dev_w(W))
+    Xd = torch.from_numpy(X.view(np.float16)).cuda()
+    fls.ensure_workspace(M, K, N)
+    good = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+    fls.fls_spmm(blob, Xd, good, M, K, N)
+    torch.cuda.synchronize()
+    ref = oracle_mod.ref_spmm_f64(W, X)
+    assert float(np.abs(good.cpu().numpy().astype(np.float64) - ref).max()) / float(np.abs(ref).max()) <= TOL
+    host = blob.cpu().numpy().view(np.uint32).copy()
+    tiles = (M // 128) * (K // 32)
+    n_off = st["bytes_offsets"] // 4
+    assert host[16 + tiles] == st["bytes_nonzeros"] // 4
+    host[16 + tiles: 16 + n_off] += 2000  # the last tile's end, and the guard entries behind it
+    slack = np.full(16384, (0x3C00 << 16) | 0, dtype=np.uint32)
+    damaged = torch.from_numpy(np.concatenate([host, slack]).view(np.uint8)).cuda()
+    for call in ("spmm", "stats"):
+        C = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+        if call == "spmm":
+            fls.fls_spmm(damaged, Xd, C, M, K, N)
+        else:
+            fls.fls_spmm_stats(damaged, st, Xd, C, M, K, N)
+        torch.cuda.synchronize()
+        # (not bit for bit: with 32 columns the waves' sums are added in the order they finish; a slack word read
+        # would add about 1 to an element of size 0.4)
+        assert float((C.float() - good.float()).abs().max()) <= TOL * float(good.float().abs().max()), call
+    fls.fls_forget()
+
+
 @pytest.mark.parametrize("M,K,N", [(7168, 4096, 16), (12288, 6144, 32)])
 def test_two_matrices_taking_turns_on_the_same_partial_sum_slots(fls, oracle_mod, M, K, N):
     """Two different matrices of one shape, multiplied in turns: both calls use the same grid, so workgroup q of
