@@ -36,8 +36,8 @@ OTHERS = ("C2", "C3")   # reported beside it in the same JSON line
 # of this script (FETCH_SIZE, then WRITE_SIZE, scaled by a copy kernel of known size), whose summaries are
 # under profiles/; the line carries the figure together with the file it was copied from, or null.
 MEASURED_TRAFFIC = {
-    "C2": (169.94e6, "profiles/spmm_C2_hbm_traffic.md (separate rocprofv3 --pmc runs, not this run)"),
-    "C4": (336.31e6, "profiles/spmm_C4_hbm_traffic.md (separate rocprofv3 --pmc runs, not this run; both kernels of the call)"),
+    "C2": (169.90e6, "profiles/spmm_C2_hbm_traffic.md (separate rocprofv3 --pmc runs, not this run)"),
+    "C4": (336.16e6, "profiles/spmm_C4_hbm_traffic.md (separate rocprofv3 --pmc runs, not this run; both kernels of the call)"),
 }
 
 
@@ -448,7 +448,7 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--config", default=HEADLINE,
-                    help=f"C1..C4, L1, L2 (OPT-175B-sized); default {HEADLINE}, the largest named single-GPU configuration")
+                    help=f"C1..C4, L1, L2 (OPT-175B-sized), S1 (C4 with 32 columns); default {HEADLINE}, the largest named single-GPU configuration")
     ap.add_argument("--no-others", action="store_true",
                     help="leave out the other named configurations (C2, C3) that the default run reports beside the headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")

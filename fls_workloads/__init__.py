@@ -100,6 +100,9 @@ CONFIGS = {
     # call is long enough for the fixed cost of a launch not to matter
     "L1": Config("L1", 49152, 12288, 16, 0.80, "magnitude", 0x5EED0006, "OPT-175B-shaped FFN up-projection"),
     "L2": Config("L2", 49152, 12288, 8, 0.70, "magnitude", 0x5EED0007, "OPT-175B-shaped FFN up-projection"),
+    # C4's matrix with 32 columns: 90 % sparsity in the passes of up to 32 columns, where the on-chip work per
+    # tile, not the stream, is the ceiling (the point the two format versions are compared on with counters)
+    "S1": Config("S1", 12288, 49152, 32, 0.90, "magnitude", 0x5EED0004, "OPT-175B-shaped FFN down-projection, 32 columns"),
 }
 
 
