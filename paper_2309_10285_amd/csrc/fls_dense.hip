@@ -4,6 +4,8 @@
 // from HBM (a lane's 8 consecutive k are one 16 B load), keeps a few tiles in flight in registers,
 // takes X fragments from L2 and accumulates with v_mfma_f32_16x16x32_f16 in fp32.  Split-K as in
 // the sparse kernel.
+#include <atomic>
+
 #include "fls_device.h"
 #include "fls_launch.h"
 
@@ -139,12 +141,12 @@ __global__ __launch_bounds__(WAVES * 64) void dense_kernel(DenseParams p) {
 
 template <int NB, int WAVES, int NS, int H>
 static hipError_t launch_dense_variant(const DenseParams& p, int grid, hipStream_t stream) {
-  static bool attr_done = false;
+  static std::atomic<bool> attr_done{false};  // per kernel variant; setting the attribute twice from two threads is harmless
   const int lds_bytes = (int)sizeof(WgReduceLds<NB>);
-  if (!attr_done) {
+  if (!attr_done.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)dense_kernel<NB, WAVES, NS, H>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
-    attr_done = true;
+    attr_done.store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL((dense_kernel<NB, WAVES, NS, H>), dim3(grid), dim3(WAVES * 64), lds_bytes, stream, p);
   return hipGetLastError();

@@ -17,6 +17,7 @@
 // Split-K: the tile sequence (band-major) is cut evenly over all waves of the grid; partial
 // bands are summed in LDS inside a workgroup and through fp32 slots in HBM between workgroups.
 // More than 32 columns: fls_spmm_wide.hip.
+#include <atomic>
 #include <type_traits>
 
 #include "fls_device.h"
@@ -288,51 +289,26 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
     ++tc;
   };
 
-  // When the workgroup's share lies inside one band (and is one column block wide, with a tile for
-  // every wave), every wave has one piece, all of the same band, and the sum needs no turns and
-  // no lock: each wave leaves its accumulators in its own tile buffer (8 KB, free once its run is
-  // over) and counts itself in; the wave that arrives last adds them up in wave order and does
-  // with the sum what the share's place in the band asks for - writes C (the whole band: the case
-  // of the band-aligned grid, and the last thing the whole chip waits for), keeps it as the
-  // band's owner, or stores it as the workgroup's partial sum.
-  const bool one_band = NB == 1 && share0 / KT == (share1 - 1) / KT && share1 - share0 >= (uint32_t)WAVES;
+  // When the workgroup's share lies inside one band (with a tile for every wave), every wave has one
+  // piece, all of the same band, and when its run is over none has anything else left to do: they
+  // meet at a barrier and share the sum.  Every wave leaves its accumulators of one column block in
+  // its tile buffer (8 KB, free by then), and wave w adds the eight buffers' row block w in wave
+  // order - a fixed order.  What happens to those 16 rows depends on the share's place in the band:
+  //  - the whole band (the band-aligned grid; the last thing the whole chip waits for): converted and
+  //    stored to C by the wave that summed them;
+  //  - the band's beginning: this workgroup is the band's owner; the row blocks go through an LDS slot
+  //    into wave 0's registers, which finishes the band after the loop, once the other workgroups'
+  //    sums are there;
+  //  - else: stored to the workgroup's partial-sum slot by the wave that summed them; wave 0 starts
+  //    the release once all eight parts have reached the L2, and publishes the slot after the loop.
+  const bool one_band = share0 / KT == (share1 - 1) / KT && share1 - share0 >= (uint32_t)WAVES;
   auto one_band_sum = [&](uint32_t band) {
-#pragma unroll
-    for (int rb = 0; rb < kRowBlocks; ++rb) *(float4v*)(tile + rb * 1024 + lane * 16) = acc[rb][0];
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    uint32_t arrived = 0;
-    if (lane == 0) arrived = __hip_atomic_fetch_add(&red->cnt[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    if (__builtin_amdgcn_readfirstlane(arrived) != (uint32_t)WAVES - 1) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-#pragma unroll
-    for (int rb = 0; rb < kRowBlocks; ++rb) acc[rb][0] = float4v{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int w = 0; w < WAVES; ++w)
-#pragma unroll
-      for (int rb = 0; rb < kRowBlocks; ++rb) acc[rb][0] += *(const float4v*)(lds + w * kWaveLds + rb * 1024 + lane * 16);
-    const bool from_start = share0 % KT == 0, to_end = share1 % KT == 0;
-    if ((from_start && to_end) || (FLS_ABLATE & 64)) {
-      store_band<NB>(p.out, acc, band, lane);
-    } else if (from_start) {
-      hs.own = true;  // finished after the loop, once the other workgroups' sums are there
-      hs.own_band = band;
-    } else {
-      store_partial<NB>(p.out, acc, blockIdx.x, lane);
-      release_begin();
-      hs.released = true;
-      hs.publish = true;
-    }
-  };
-
-  // When the share is exactly one whole band (the band-aligned grid: no partial sum leaves the
-  // workgroup) every wave has one piece of it, and the last thing the whole chip waits for is this
-  // sum.  All waves then meet at a barrier (none has anything else left to do) and share the work:
-  // every wave leaves its accumulators of one column block in its tile buffer, and wave w adds the
-  // eight buffers' row block w in wave order - a fixed order - converts and stores those 16 rows of C.
-  const bool whole_band = share0 % KT == 0 && share1 - share0 == KT && KT >= (uint32_t)WAVES;
-  auto whole_band_sum = [&](uint32_t band) {
     static_assert(WAVES == kRowBlocks, "one row block per wave");
+    const bool from_start = share0 % KT == 0, to_end = share1 % KT == 0;
+    const bool whole = (from_start && to_end) || (FLS_ABLATE & 64);
     const uint32_t col = lane & 15, rsub = (lane >> 4) * 4;
+    const __amdgpu_buffer_rsrc_t mine = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(p.out.parts + (size_t)blockIdx.x * (NB * kAccPerBlock)), 0, NB * kAccPerBlock * 4, kBufferFlags);
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       if (nb > 0) __syncthreads();  // every wave is done reading the buffers of the column block before
@@ -342,12 +318,39 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
       float4v sum = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int w = 0; w < WAVES; ++w) sum += *(const float4v*)(lds + w * kWaveLds + wave * 1024 + lane * 16);
-      const uint32_t n = p.out.n0 + nb * 16 + col;
-      if (n < p.out.N) {
-        half4 h;
+      if (whole) {
+        const uint32_t n = p.out.n0 + nb * 16 + col;
+        if (n < p.out.N) {
+          half4 h;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) h[r] = (_Float16)sum[r];
-        *(half4*)(p.out.C + (size_t)n * p.out.M + band * kTileM + wave * 16 + rsub) = h;
+          for (int r = 0; r < 4; ++r) h[r] = (_Float16)sum[r];
+          *(half4*)(p.out.C + (size_t)n * p.out.M + band * kTileM + wave * 16 + rsub) = h;
+        }
+      } else if (from_start) {
+        red->slot[0][(nb * kRowBlocks + wave) * 64 + lane] = sum;
+      } else {
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, sum), mine, ((nb * kRowBlocks + wave) * 64 + lane) * 16,
+                                               0, kAuxCoherent);
+      }
+    }
+    if (whole) return;
+    if (from_start) {
+      __syncthreads();
+      if (wave == 0) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int rb = 0; rb < kRowBlocks; ++rb) acc[rb][nb] = red->slot[0][(nb * kRowBlocks + rb) * 64 + lane];
+        hs.own = true;
+        hs.own_band = band;
+      }
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's part of the partial sum has reached the L2
+      __syncthreads();
+      if (wave == 0) {
+        release_begin();
+        hs.released = true;
+        hs.publish = true;
       }
     }
   };
@@ -367,8 +370,7 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 #pragma unroll
     for (int i = 0; i < NS - 1; ++i)
       if (tc < pend) step(s[i], x[i], sb[i], se[i]);
-    if (whole_band) whole_band_sum(bandc);
-    else if (one_band) one_band_sum(bandc);
+    if (one_band) one_band_sum(bandc);
     else hand_over(bandc, pend - piece0);
     ktc += pend - piece0;
     if (ktc == KT) {
@@ -394,13 +396,13 @@ constexpr int ring_depth(int NB, int WAVES, int R) {
 template <int NB, int WAVES, int R, int FMT>
 static hipError_t launch_variant(const SpmmParams& p, int grid, hipStream_t stream) {
   constexpr int NS = ring_depth(NB, WAVES, R);
-  static bool attr_done = false;
+  static std::atomic<bool> attr_done{false};  // per kernel variant; setting the attribute twice from two threads is harmless
   const int lds_bytes = WAVES * wave_lds(NB) + (int)sizeof(WgReduceLds<NB>);
-  if (!attr_done) {
+  if (!attr_done.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)spmm_kernel<NB, WAVES, R, NS, FMT>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        lds_bytes);
     if (e != hipSuccess) return e;
-    attr_done = true;
+    attr_done.store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL((spmm_kernel<NB, WAVES, R, NS, FMT>), dim3(grid), dim3(WAVES * 64), lds_bytes, stream, p);
   return hipGetLastError();

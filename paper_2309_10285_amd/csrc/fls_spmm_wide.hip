@@ -22,6 +22,7 @@
 // the tile, extract the next one, read its fragments, refill the ring, X chunk traffic) dealt out
 // between them, and they work on fragments that were read during the step before.  The shape is
 // v_mfma_f32_32x32x16_f16 (16 per tile).
+#include <atomic>
 #include <type_traits>
 
 #include "fls_device.h"
@@ -505,12 +506,12 @@ __global__ __launch_bounds__(256) void wide_reduce_kernel(WideParams p) {
 
 template <int R, int NS>
 static hipError_t launch_wide_variant(WideParams p, int cus, hipStream_t stream) {
-  static bool attr_done = false;
+  static std::atomic<bool> attr_done{false};  // per kernel variant; setting the attribute twice from two threads is harmless
   constexpr int kLds = wide_lds_bytes<NS>();
-  if (!attr_done) {
+  if (!attr_done.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)spmm_wide_kernel<R, NS>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
     if (e != hipSuccess) return e;
-    attr_done = true;
+    attr_done.store(true, std::memory_order_release);
   }
   const uint32_t quads = (p.bands + 3u) / 4u;
   p.S = wide_quad_slices(p.bands, p.G, p.KT, cus, NS);
