@@ -1,6 +1,6 @@
 /*
- * CPU oracle, format version 2: Tiled-CSL with the in-tile locations stored as 8-bit distances
- * (3 bytes per nonzero instead of 4).
+ * CPU oracle, format version 2: Tiled-CSL with the in-tile locations of four entries packed into one
+ * word - the first one in full, the others as 6-bit distances (3 bytes per nonzero instead of 4).
  *
  * TEST INFRASTRUCTURE ONLY, like fls_oracle.c: the slow, plain definition the HIP library's
  * version-2 compressor is checked against bit for bit.  Nothing in the product path may call it,
@@ -11,13 +11,13 @@
  * of the sparse indices out: with them the sparse load moves 4 B per kept weight, so it only breaks
  * even with the dense load at 50 % sparsity.  Version 2 is this build's own narrowing of that
  * overhead: a tile's entries are kept in ascending location order (Alg. 3's order before the bank
- * reordering) and each carries the distance from the entry before it, in 8 bits.  What the format
+ * reordering) and go in groups of four that share one word of location data.  What the format
  * decodes to - the dense tile - is unchanged, so the SpMM definition (fls_oracle.c) is too.
  *
  * Parity status: flso2_compress / flso2_decompress / flso2_inspect are pinned by a tile encoded by
  * hand from the rules below (tests/golden/tiled_csl_v2_hand_tile.json), by an independent decoder
- * written in the test, by bit-exact round trips (special values, empty and full tiles, gaps beyond
- * 255 locations) and by closed-form sizes.  The format itself is this build's, not the paper's.
+ * written in the test, by bit-exact round trips (special values, empty and full tiles, gaps at and
+ * beyond 63 locations) and by closed-form sizes.  The format itself is this build's, not the paper's.
  *
  * Blob (little endian):
  *   [0,64)   header as in version 1 with magic 'FLS2', version 2, pad = 4 (entries per group),
@@ -26,16 +26,24 @@
  *            entries from num_tiles on repeat total_words); every offset is a multiple of 3
  *   then     NonZeros: groups of four entries in three words:
  *              word 0 = value0 | value1 << 16,  word 1 = value2 | value3 << 16,
- *              word 2 = dist0 | dist1 << 8 | dist2 << 16 | dist3 << 24
- *   The entries of a tile, in order, walk a location counter that starts at 0: an entry's location is the
- *   counter plus its distance, and becomes the new counter.  Locations are those of version 1
- *   (loc = (y/8)*(tile_m*8) + x*8 + y%8).  Three kinds of entries:
+ *              word 2 = loc0 | dist1 << 12 | dist2 << 18 | dist3 << 24   (12 + 3 x 6 bits; bits 30, 31 are 0)
+ *            loc0 = the location of entry 0, distK = location of entry K minus location of entry K - 1.
+ *   Locations are those of version 1 (loc = (y/8)*(tile_m*8) + x*8 + y%8; a tile has at most 4096).
+ *   The entries of a tile, in ascending location, are of three kinds:
  *     - a stored element (16-bit pattern != 0x0000) at its location;
- *     - a bridge, value 0x0000 and distance 255, wherever the next stored element lies more than 255
- *       locations ahead of the counter: it names a location between two stored elements, which is
- *       empty, so decoding it (a zero written to a zero) changes nothing;
+ *     - a bridge, value 0x0000, wherever the next stored element lies more than 63 locations behind
+ *       the entry before it (behind location 0 for the first): bridges stand 63, 126, ... locations
+ *       behind that entry until 63 or fewer are left.  A bridge names a location between two stored
+ *       elements, which is empty, so decoding it (a zero written to a zero) changes nothing.  The
+ *       rule is the same wherever in a group the next entry falls, also where it starts a group and
+ *       would not need it: the number of entries of a tile then does not depend on how they fall
+ *       into groups;
  *     - padding up to a multiple of four entries, value 0x0000 and distance 1: the locations behind
- *       the tile's last stored element (empty), possibly up to three past the end of the tile.
+ *       the tile's last entry (empty), possibly up to three past the end of the tile.  A group never
+ *       starts with padding.
+ *   A group is decoded by itself - nothing is carried from one group to the next - which is what the
+ *   format is for: on the GPU a lane takes a group, and its four scatter addresses cost it three
+ *   additions, with no sum across lanes.
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -46,6 +54,7 @@
 #define FLSO2_VERSION 2u
 #define FLSO2_HEADER_BYTES 64u
 #define FLSO2_GROUP 4u /* entries per group */
+#define FLSO2_REACH 63u /* largest distance a 6-bit field holds */
 
 static void put32(uint8_t* p, uint32_t v) { memcpy(p, &v, 4); }
 static void put64(uint8_t* p, uint64_t v) { memcpy(p, &v, 8); }
@@ -64,19 +73,19 @@ static uint64_t round_up64(uint64_t v, uint64_t m) { return (v + m - 1) / m * m;
 static int geometry2_ok(int64_t M, int64_t K, uint32_t tile_m, uint32_t tile_k) {
   if (M <= 0 || K <= 0 || tile_m == 0 || tile_k == 0) return 0;
   if (tile_k % 8 != 0) return 0;
-  if ((uint64_t)tile_m * tile_k > 65535u) return 0;
+  if ((uint64_t)tile_m * tile_k > 4096u) return 0; /* loc0 has 12 bits */
   if (M % tile_m != 0 || K % tile_k != 0) return 0;
   return 1;
 }
 
 /*
- * The entries of tile (i, j), in order: values to val[], distances to dist[] (each with room for
- * tile_m*tile_k + tile_m*tile_k/255 + 4 entries).  Returns the number of entries (a multiple of four);
- * *stored = elements stored.
+ * The entries of tile (i, j), in order: values to val[], locations to loc[] (each with room for
+ * tile_m*tile_k + 8 entries: a bridge stands for 63 empty locations, so entries never outnumber
+ * locations).  Returns the number of entries (a multiple of four); *stored = elements stored.
  */
 static uint32_t tile_entries(const uint16_t* W, int64_t K, uint64_t i, uint64_t j, uint32_t tile_m,
-                             uint32_t tile_k, uint16_t* val, uint8_t* dist, uint64_t* stored) {
-  uint32_t n = 0, counter = 0;
+                             uint32_t tile_k, uint16_t* val, uint32_t* locs, uint64_t* stored) {
+  uint32_t n = 0, last = 0; /* last = location of the entry before (0 before the first) */
   uint64_t nz = 0;
   /* ascending location = K-chunk of 8, then row, then position in the chunk */
   for (uint32_t c = 0; c < tile_k / 8; ++c)
@@ -86,21 +95,22 @@ static uint32_t tile_entries(const uint16_t* W, int64_t K, uint64_t i, uint64_t 
         const uint16_t bits = W[(i * tile_m + x) * (uint64_t)K + j * tile_k + y];
         if (bits == 0) continue;
         const uint32_t loc = c * (tile_m * 8u) + x * 8u + e;
-        while (loc - counter > 255u) { /* bridge over a long run of empty locations */
+        while (loc - last > FLSO2_REACH) { /* bridge over a long run of empty locations */
+          last += FLSO2_REACH;
           val[n] = 0;
-          dist[n] = 255;
-          counter += 255u;
+          locs[n] = last;
           n++;
         }
         val[n] = bits;
-        dist[n] = (uint8_t)(loc - counter);
-        counter = loc;
+        locs[n] = loc;
+        last = loc;
         n++;
         nz++;
       }
   while (n % FLSO2_GROUP != 0) { /* padding: the next (empty) locations */
+    last += 1;
     val[n] = 0;
-    dist[n] = 1;
+    locs[n] = last;
     n++;
   }
   *stored = nz;
@@ -117,15 +127,15 @@ size_t flso2_compress(const uint16_t* W, int64_t M, int64_t K, uint32_t tile_m, 
   const uint64_t tiles_k = (uint64_t)K / tile_k;
   const uint64_t num_tiles = ((uint64_t)M / tile_m) * tiles_k;
   const uint64_t n_off = round_up64(num_tiles + 4, 16);
-  const size_t room = (size_t)tile_m * tile_k + (size_t)tile_m * tile_k / 255 + 8;
+  const size_t room = (size_t)tile_m * tile_k + 8;
   uint16_t* val = (uint16_t*)malloc(room * sizeof(uint16_t));
-  uint8_t* dist = (uint8_t*)malloc(room);
+  uint32_t* locs = (uint32_t*)malloc(room * sizeof(uint32_t));
 
   /* pass 1: sizes */
   uint64_t nnz = 0, total_words = 0, max_tile_words = 0;
   for (uint64_t t = 0; t < num_tiles; ++t) {
     uint64_t nz;
-    const uint32_t n = tile_entries(W, K, t / tiles_k, t % tiles_k, tile_m, tile_k, val, dist, &nz);
+    const uint32_t n = tile_entries(W, K, t / tiles_k, t % tiles_k, tile_m, tile_k, val, locs, &nz);
     const uint64_t words = (uint64_t)n / FLSO2_GROUP * 3u;
     nnz += nz;
     total_words += words;
@@ -134,7 +144,7 @@ size_t flso2_compress(const uint16_t* W, int64_t M, int64_t K, uint32_t tile_m, 
   const size_t need = (size_t)(FLSO2_HEADER_BYTES + 4 * n_off + 4 * total_words);
   if (total_words > 0xffffffffull || out == NULL || cap < need) {
     free(val);
-    free(dist);
+    free(locs);
     return total_words > 0xffffffffull ? 0 : need;
   }
 
@@ -157,19 +167,19 @@ size_t flso2_compress(const uint16_t* W, int64_t M, int64_t K, uint32_t tile_m, 
   for (uint64_t t = 0; t < num_tiles; ++t) {
     uint64_t nz;
     put32(offs + 4 * t, (uint32_t)pos);
-    const uint32_t n = tile_entries(W, K, t / tiles_k, t % tiles_k, tile_m, tile_k, val, dist, &nz);
+    const uint32_t n = tile_entries(W, K, t / tiles_k, t % tiles_k, tile_m, tile_k, val, locs, &nz);
     for (uint32_t g = 0; g < n / FLSO2_GROUP; ++g) {
       const uint16_t* v = val + 4 * g;
-      const uint8_t* d = dist + 4 * g;
+      const uint32_t* l = locs + 4 * g;
       put32(nzw + 4 * (pos + 0), (uint32_t)v[0] | ((uint32_t)v[1] << 16));
       put32(nzw + 4 * (pos + 1), (uint32_t)v[2] | ((uint32_t)v[3] << 16));
-      put32(nzw + 4 * (pos + 2), (uint32_t)d[0] | ((uint32_t)d[1] << 8) | ((uint32_t)d[2] << 16) | ((uint32_t)d[3] << 24));
+      put32(nzw + 4 * (pos + 2), l[0] | ((l[1] - l[0]) << 12) | ((l[2] - l[1]) << 18) | ((l[3] - l[2]) << 24));
       pos += 3;
     }
   }
   for (uint64_t t = num_tiles; t < n_off; ++t) put32(offs + 4 * t, (uint32_t)pos);
   free(val);
-  free(dist);
+  free(locs);
   return need;
 }
 
@@ -214,23 +224,28 @@ int flso2_decompress(const uint8_t* blob, size_t bytes, uint16_t* W, int64_t M, 
     const uint64_t i = t / tiles_k, j = t % tiles_k;
     const uint32_t a = get32(offs + 4 * t), b = get32(offs + 4 * (t + 1));
     if (b < a || b > h[11] || a % 3 != 0 || b % 3 != 0) return -7;
-    uint32_t counter = 0;
+    uint32_t behind = 0; /* one past the location of the entry before: locations ascend through the tile */
     for (uint32_t q = a; q < b; q += 3) {
       const uint32_t w0 = get32(nzw + 4 * (uint64_t)q), w1 = get32(nzw + 4 * (uint64_t)(q + 1)), w2 = get32(nzw + 4 * (uint64_t)(q + 2));
       const uint16_t v[4] = {(uint16_t)w0, (uint16_t)(w0 >> 16), (uint16_t)w1, (uint16_t)(w1 >> 16)};
+      if (w2 >> 30) return -8;
+      uint32_t loc = 0;
       for (int e = 0; e < 4; ++e) {
-        counter += (w2 >> (8 * e)) & 0xffu;
+        if (e == 0) loc = w2 & 0xfffu;
+        else loc += (w2 >> (6 + 6 * e)) & 0x3fu;
+        if (loc < behind) return -12; /* entries ascend: a distance of 0 is not an entry */
+        behind = loc + 1;
         if (v[e] == 0) continue; /* bridge or padding */
-        if (counter >= elems) return -9;
-        const uint32_t c = counter / (tile_m * 8u);
-        const uint32_t x = (counter % (tile_m * 8u)) / 8u;
-        const uint32_t y = c * 8u + counter % 8u;
+        if (loc >= elems) return -9;
+        const uint32_t c = loc / (tile_m * 8u);
+        const uint32_t x = (loc % (tile_m * 8u)) / 8u;
+        const uint32_t y = c * 8u + loc % 8u;
         uint16_t* dst = &W[(i * tile_m + x) * (uint64_t)K + j * tile_k + y];
         if (*dst != 0) return -10; /* a location may be given once */
         *dst = v[e];
       }
     }
-    if (counter > elems + 3u) return -11;
+    if (behind > elems + 3u) return -11;
   }
   return 0;
 }

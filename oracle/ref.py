@@ -14,7 +14,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "fls_oracle.c")
-_SRC_V2 = os.path.join(_HERE, "fls_oracle_v2.c")  # format version 2 (8-bit location distances)
+_SRC_V2 = os.path.join(_HERE, "fls_oracle_v2.c")  # format version 2 (groups of four entries, 6-bit location distances)
 _LIB = os.path.join(_HERE, "libfls_oracle.so")
 _lib = None
 
@@ -137,7 +137,7 @@ def ref_decompress(blob, M, K):
 
 
 def ref_compress_v2(W, tile_m=TILE_M, tile_k=TILE_K):
-    """Dense masked W (uint16 [M, K]) -> format-version-2 blob (uint8 array): locations as 8-bit distances."""
+    """Dense masked W (uint16 [M, K]) -> format-version-2 blob (uint8 array): groups of four entries, first location in full, then 6-bit distances."""
     W = np.ascontiguousarray(W, dtype=np.uint16)
     M, K = W.shape
     lib = _load()

@@ -1,8 +1,9 @@
-"""Pins of the oracle's format version 2 (Tiled-CSL with 8-bit location distances, 3 bytes per nonzero).
+"""Pins of the oracle's format version 2 (Tiled-CSL in groups of four entries that share one word of locations:
+the first in full, the others as 6-bit distances; 3 bytes per nonzero).
 
 What fixes it besides itself: a tile encoded by hand from the format's rules (tests/golden/), a decoder written
 here independently of the oracle's, bit-exact round trips on the cases a plausible mistake breaks (a gap of
-exactly 255 / 256 / 510 / 511 locations, a first element beyond location 255, the last location of a tile,
+exactly 63 / 64 / 126 / 127 locations, a first element beyond location 63, the last location of a tile,
 empty and full tiles, -0.0 / NaN / Inf / subnormal patterns), and sizes from a closed form computed with numpy
 from the sorted locations."""
 import json
@@ -46,8 +47,11 @@ def _independent_decode(blob, M, K):
         i, j = divmod(t, K // tile_k)
         g = words[offs[t]:offs[t + 1]].reshape(-1, 3)
         vals = np.stack([g[:, 0] & 0xFFFF, g[:, 0] >> 16, g[:, 1] & 0xFFFF, g[:, 1] >> 16], axis=1).reshape(-1)
-        dist = np.stack([(g[:, 2] >> s) & 0xFF for s in (0, 8, 16, 24)], axis=1).reshape(-1)
-        loc = np.cumsum(dist.astype(np.int64))
+        assert not (g[:, 2] >> 30).any()
+        # every group by itself: its first location, then three distances added up
+        steps = np.stack([g[:, 2] & 0xFFF] + [(g[:, 2] >> s) & 0x3F for s in (12, 18, 24)], axis=1).astype(np.int64)
+        loc = np.cumsum(steps, axis=1).reshape(-1)
+        assert (np.diff(loc) > 0).all()  # ascending through the tile, group after group
         keep = vals != 0
         loc, vals = loc[keep], vals[keep]
         assert (loc < tile_m * tile_k).all()
@@ -74,8 +78,8 @@ def test_hand_encoded_tile(oracle_mod):
 def _closed_form_words(W, tile_m, tile_k):
     total, longest = 0, 0
     for loc, _ in _locs(W, tile_m, tile_k):
-        gaps = np.diff(np.concatenate([[0], loc]))                      # distance of every stored element from the counter
-        bridges = int(np.where(gaps > 0, (gaps - 1) // 255, 0).sum())   # 255-steps that fit strictly before it
+        gaps = np.diff(np.concatenate([[0], loc]))                     # distance of every stored element from the entry before
+        bridges = int(np.where(gaps > 0, (gaps - 1) // 63, 0).sum())   # steps of 63 that fit strictly before it
         words = -(-(loc.size + bridges) // 4) * 3
         total += words
         longest = max(longest, words)
@@ -104,15 +108,15 @@ def test_round_trip_and_sizes_random(oracle_mod, beta):
 
 
 def test_gap_edges_and_special_values(oracle_mod):
-    """One 128 x 32 tile per case: gaps of exactly 255 (no bridge), 256 (one), 510 (one), 511 (two); a first
-    element at location 255 / 256 / 4095; the tile's last location; special bit patterns."""
+    """One 128 x 32 tile per case: gaps of exactly 63 (no bridge), 64 (one), 126 (one), 127 (two); a first
+    element at location 63 / 64 / 4095; the tile's last location; special bit patterns."""
     def at(loc):  # location -> (row, column) of a 128 x 32 tile
         return (loc % 1024) // 8, (loc // 1024) * 8 + loc % 8
 
-    cases = {"gaps": [0, 255, 511, 1021, 1532, 4095], "late-start-255": [255, 256], "late-start-256": [256],
+    cases = {"gaps": [0, 63, 127, 253, 380, 4095], "late-start-63": [63, 64], "late-start-64": [64],
              "only-last": [4095], "first-and-last": [0, 4095], "dense-run": list(range(1000, 1300))}
-    expected_bridges = {"gaps": 0 + 0 + 1 + 1 + 2 + (4095 - 1532 - 1) // 255, "late-start-255": 0, "late-start-256": 1,
-                        "only-last": (4095 - 1) // 255, "first-and-last": (4095 - 1) // 255, "dense-run": (1000 - 1) // 255}
+    expected_bridges = {"gaps": 0 + 0 + 1 + 1 + 2 + (4095 - 380 - 1) // 63, "late-start-63": 0, "late-start-64": 1,
+                        "only-last": (4095 - 1) // 63, "first-and-last": (4095 - 1) // 63, "dense-run": (1000 - 1) // 63}
     special = [0x8000, 0x7C00, 0xFC00, 0x7E00, 0xFFFF, 0x0001, 0x83FF, 0x3C00]
     for name, locs in cases.items():
         W = np.zeros((128, 32), dtype=np.uint16)
@@ -147,3 +151,13 @@ def test_malformed_blobs_are_rejected(oracle_mod):
         oracle_mod.ref_decompress_v2(blob[:-12], 128, 64)  # truncated
     with pytest.raises(ValueError):
         oracle_mod.ref_decompress_v2(blob, 256, 64)        # another shape
+    info = oracle_mod.ref_inspect_v2(blob)
+    w2 = 64 + info["bytes_offsets"] + 8                    # the first group's word of locations
+    bad = blob.copy()
+    bad[w2:w2 + 4].view(np.uint32)[0] &= ~np.uint32(0x3F << 12)  # a distance of 0: the same location twice
+    with pytest.raises(ValueError):
+        oracle_mod.ref_decompress_v2(bad, 128, 64)
+    bad = blob.copy()
+    bad[w2:w2 + 4].view(np.uint32)[0] |= np.uint32(1 << 31)      # a bit that no field owns
+    with pytest.raises(ValueError):
+        oracle_mod.ref_decompress_v2(bad, 128, 64)
