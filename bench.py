@@ -347,7 +347,7 @@ def measure_config(name, args, with_dense, with_cpu):
                      "roof_us": {"hbm_8TBps": round(t_hbm_us, 2), "mfma_f16_2.5PFLOPs": round(t_mfma_us, 2)}},
     }
 
-    # the same matrix in format version 2 (8-bit location distances, 3 bytes per nonzero), timed the same way and
+    # the same matrix in format version 2 (four entries share a word of locations, 3 bytes per nonzero), timed the same way and
     # stated against its own bytes
     if args.v2:
         W2 = torch.from_numpy(Wb.view(np.float16)).cuda()

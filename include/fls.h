@@ -37,7 +37,7 @@ extern "C" {
 #define FLS_PAD_WORDS 4u /* a tile's run is padded to a multiple of this many words */
 #define FLS_MAX_N 8192 /* the skinny case is N <= 256; wider N runs as passes of 64 columns (Sec. 6.2, non-skinny shapes) */
 #define FLS_FORMAT_VERSION 1u
-#define FLS_FORMAT_VERSION_2 2u /* locations as 8-bit distances, 3 bytes per entry: fls_compress_v2 */
+#define FLS_FORMAT_VERSION_2 2u /* four entries share a word of locations, 3 bytes per entry: fls_compress_v2 */
 #define FLS_HEADER_BYTES 64u
 
 enum {
@@ -105,20 +105,21 @@ int fls_compress(const void* W_dev, int64_t M, int64_t K, void* out_dev, size_t 
                  int order_policy, fls_stats* stats_host, fls_stream_t stream);
 
 /*
- * Format version 2: the same tiles, walk and stored elements, with the 16-bit location of every word
- * replaced by an 8-bit distance - 3 bytes per nonzero instead of 4.  The paper's byte model leaves
+ * Format version 2: the same tiles, walk and stored elements, with the 16-bit locations of four entries
+ * packed into one word - 3 bytes per nonzero instead of 4.  The paper's byte model leaves
  * the index bytes out (footnote under Eq. 2, Sec. 3.2.2) while its format pays 2 of them per kept
  * weight (Sec. 4.3.2); this is this build's own narrowing of that overhead.  Blob:
  *   header as above with magic "FLS2", version 2, pad_words 4 (entries per group), order_policy 0
  *   TileOffsets as above (u32 offsets in 32-bit words, all multiples of 3)
  *   NonZeros: groups of four entries in three words: word 0 = value0 | value1 << 16,
- *            word 1 = value2 | value3 << 16, word 2 = dist0 | dist1 << 8 | dist2 << 16 | dist3 << 24
- *   The entries of a tile, in order, walk a location counter that starts at 0: an entry's location is
- *   the counter plus its distance and becomes the new counter.  Entries are the stored elements in
- *   ascending location; a bridge (value 0x0000, distance 255) wherever the next stored element lies
- *   more than 255 locations ahead - it names an empty location; padding (value 0x0000, distance 1)
- *   up to a multiple of four entries - the empty locations behind the tile's last stored element,
- *   at most three past the end of the tile.
+ *            word 1 = value2 | value3 << 16, word 2 = loc0 | dist1 << 12 | dist2 << 18 | dist3 << 24
+ *            (loc0: the location of entry 0, 12 bits; distK: location of entry K minus location of
+ *            entry K - 1, 6 bits; bits 30 and 31 are 0).  A group decodes by itself.
+ *   The entries of a tile are the stored elements in ascending location; a bridge (value 0x0000)
+ *   every 63 locations wherever the next stored element lies more than 63 locations behind the entry
+ *   before it (behind location 0 for the first) - it names an empty location - whether or not the
+ *   next entry starts a group; padding (value 0x0000, distance 1) up to a multiple of four entries -
+ *   the empty locations behind the tile's last entry, at most three past the end of the tile.
  * fls_compress_v2 is fls_compress for this format (same arguments without the order policy, same
  * errors, same waiting); fls_compress_bound_v2 its capacity bound.  fls_inspect and fls_spmm take
  * blobs of either version (fls_spmm tells them apart by the header); a version-2 blob is multiplied

@@ -160,7 +160,7 @@ def fls_compress_bound_v2(M, K):
 
 
 def fls_compress_v2(W, out=None):
-    """fls_compress for format version 2 (8-bit location distances, 3 bytes per nonzero)."""
+    """fls_compress for format version 2 (four entries share a word of locations, 3 bytes per nonzero)."""
     import torch
 
     assert W.is_cuda and W.dtype == torch.float16 and W.is_contiguous() and W.dim() == 2

@@ -179,13 +179,14 @@ hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream) {
 
 // ---------------------------------------------------------------- format version 2
 //
-// Locations as 8-bit distances, three bytes per entry (the index bytes that the footnote under the
-// paper's Eq. 2 leaves out of its model are what version 1 pays in full): a tile's entries walk a
-// location counter from 0, groups of four entries take three words (two of values, one of
-// distances).  An entry is a stored element, a bridge (value 0, distance 255) where the next
-// stored element lies more than 255 locations ahead, or padding (value 0, distance 1) up to a
-// multiple of four.  Same three kernels: count (entries per tile, bridges included; stored
-// elements summed into the header), scan, emit.
+// Three bytes per entry (the index bytes that the footnote under the paper's Eq. 2 leaves out of
+// its model are what version 1 pays in full): a tile's entries, in ascending location, go in
+// groups of four that take three words - two of values, one with the first entry's location in
+// 12 bits and the other three as 6-bit distances from the entry before.  An entry is a stored
+// element, a bridge (value 0) every 63 locations where the next stored element lies more than 63
+// behind the entry before it, or padding (value 0, distance 1) up to a multiple of four.  Same
+// three kernels: count (entries per tile, bridges included; stored elements summed into the
+// header), scan, emit.
 
 constexpr uint32_t kMagic2 = 0x32534C46u;  // "FLS2"
 constexpr uint32_t kGroup = 4;              // entries per group of three words
@@ -203,17 +204,20 @@ __device__ __forceinline__ uint32_t wave_inclusive_max(uint32_t v, int lane) {
 // One wave walks tile (band, kt) in location order, as compress_emit_kernel does: per step a lane
 // holds the 8 halves of one (row, K-chunk) cell, i.e. 8 consecutive locations.  Returns the number
 // of entries before padding; *stored = stored elements seen by this lane.  With EMIT the entries
-// (and the padding) are written to `dst`, the tile's first group.
+// (and the padding) are put together in `stage`, the tile's words in LDS, zeroed by the caller:
+// entry e is entry e & 3 of group e >> 2, whose three words different lanes fill, so values and
+// location fields are OR-ed in.
+constexpr uint32_t kReach2 = 63;  // largest distance a 6-bit field holds: a bridge entry every 63 empty locations
 template <bool EMIT>
 __device__ __forceinline__ uint32_t walk_tile_v2(const CompressParams& p, uint32_t band, uint32_t kt, int lane,
-                                                 unsigned char* dst, uint32_t* stored) {
-  auto put = [&](uint32_t e, uint32_t bits, uint32_t dist) {
-    unsigned char* g = dst + (size_t)(e >> 2) * 12u;
-    *(uint16_t*)(g + (e & 3u) * 2u) = (uint16_t)bits;
-    g[8u + (e & 3u)] = (unsigned char)dist;
+                                                 uint32_t* stage, uint32_t* stored) {
+  auto put = [&](uint32_t e, uint32_t bits, uint32_t loc, uint32_t dist) {
+    const uint32_t g = e >> 2, k = e & 3u;
+    atomicOr(&stage[g * 3u + (k >> 1)], (k & 1u) ? bits << 16 : bits);
+    atomicOr(&stage[g * 3u + 2u], k == 0 ? loc : dist << (6u + 6u * k));  // the group's first location in full, then distances
   };
   uint32_t pos = 0;      // entries so far
-  uint32_t counter = 0;  // the location counter behind the steps done so far
+  uint32_t counter = 0;  // the location of the last entry of the steps done so far (0 before the first)
   uint32_t nz = 0;
   for (uint32_t c = 0; c < kTileK / 8; ++c) {
     for (uint32_t half = 0; half < kTileM / 64; ++half) {
@@ -222,8 +226,8 @@ __device__ __forceinline__ uint32_t walk_tile_v2(const CompressParams& p, uint32
       const uint32_t mask = nonzero_mask(v);
       const uint32_t cnt = __popc(mask);
       const uint32_t loc0 = c * (kTileM * 8) + row * 8;
-      // the counter this lane's first element starts from: the last stored location in the lanes
-      // before it (0 stands for "none", which is also where the counter starts)
+      // the entry this lane's first element follows: the last stored location in the lanes
+      // before it (0 stands for "none", which is also what the first element of a tile follows)
       const uint32_t last = cnt ? loc0 + (31u - (uint32_t)__clz((int)mask)) : 0u;
       const uint32_t run_max = wave_inclusive_max(last, lane);
       uint32_t prev = __shfl_up(run_max, 1, 64);
@@ -231,20 +235,20 @@ __device__ __forceinline__ uint32_t walk_tile_v2(const CompressParams& p, uint32
       prev = prev > counter ? prev : counter;
       const uint32_t first = loc0 + (uint32_t)__builtin_ctz(mask | 0x100u);
       const uint32_t gap = first - prev;
-      const uint32_t bridges = (cnt && gap > 0u) ? (gap - 1u) / 255u : 0u;
+      const uint32_t bridges = (cnt && gap > 0u) ? (gap - 1u) / kReach2 : 0u;
       const uint32_t entries = cnt + bridges;
       const uint32_t incl = wave_inclusive_scan(entries, lane);
       if (EMIT) {
         uint32_t slot = pos + incl - entries, cur = prev;
         for (uint32_t b = 0; b < bridges; ++b) {
-          put(slot++, 0u, 255u);
-          cur += 255u;
+          cur += kReach2;
+          put(slot++, 0u, cur, kReach2);
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           if (mask >> e & 1u) {
             const uint32_t bits = (e & 1) ? (v[e >> 1] >> 16) : (v[e >> 1] & 0xffffu);
-            put(slot++, bits, loc0 + e - cur);
+            put(slot++, bits, loc0 + e, loc0 + e - cur);
             cur = loc0 + e;
           }
         }
@@ -256,8 +260,9 @@ __device__ __forceinline__ uint32_t walk_tile_v2(const CompressParams& p, uint32
     }
   }
   if (EMIT) {
+    // padding never starts a group, so only its distance (1) goes in
     const uint32_t padded_entries = (pos + kGroup - 1) / kGroup * kGroup;
-    if (pos + lane < padded_entries) put(pos + lane, 0u, 1u);
+    if (pos + lane < padded_entries) put(pos + lane, 0u, 0u, 1u);
   }
   *stored = nz;
   return pos;
@@ -329,12 +334,22 @@ __global__ __launch_bounds__(1024) void compress2_scan_kernel(CompressParams p) 
   }
 }
 
+// A wave per tile: the tile's words are put together in LDS (at most 1024 groups of 12 B) and copied out.
 __global__ __launch_bounds__(256) void compress2_emit_kernel(CompressParams p) {
+  __shared__ uint32_t stages[4][kTileM * kTileK / kGroup * 3];
   const int lane = threadIdx.x & 63;
-  const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const uint32_t wave = threadIdx.x >> 6;
+  const uint32_t t = blockIdx.x * 4 + wave;
   if (t >= p.T) return;
+  uint32_t* stage = stages[wave];
+  const uint32_t begin = offs_of(p)[t], nwords = offs_of(p)[t + 1] - begin;
+  for (uint32_t i = lane; i < nwords; i += 64) stage[i] = 0u;
+  __builtin_amdgcn_wave_barrier();  // (LDS executes a wave's operations in order; this keeps the compiler from moving them)
   uint32_t nz;
-  walk_tile_v2<true>(p, t / p.KT, t % p.KT, lane, (unsigned char*)(words_of(p) + offs_of(p)[t]), &nz);
+  walk_tile_v2<true>(p, t / p.KT, t % p.KT, lane, stage, &nz);
+  __builtin_amdgcn_wave_barrier();
+  uint32_t* dst = words_of(p) + begin;
+  for (uint32_t i = lane; i < nwords; i += 64) dst[i] = stage[i];
 }
 
 static CompressParams make_params(const CompressLaunch& a) {

@@ -35,7 +35,7 @@ struct CompressLaunch {
   unsigned char* out;  // blob
   uint32_t M, K;
   uint32_t policy;
-  uint32_t version;  // 1: 32-bit words (value, location); 2: 8-bit location distances, three bytes per entry
+  uint32_t version;  // 1: 32-bit words (value, location); 2: groups of four entries in three words, three bytes per entry
 };
 
 // Columns are processed in groups, one pass over W per group.  The dense baseline and the sparse

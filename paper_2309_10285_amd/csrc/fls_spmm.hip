@@ -46,11 +46,13 @@ struct SpmmParams {
 };
 
 // FMT = format version of the blob: 1 = 32-bit words (value, location), R rounds of 256 words staged
-// per tile; 2 = groups of four entries in three words with 8-bit location distances, R rounds of 64
-// groups (256 entries, 192 words) staged per tile.
+// per tile; 2 = groups of four entries in three words (the first location in full, three 6-bit
+// distances), R rounds of 64 groups (256 entries, 192 words) staged per tile.  A stage register holds
+// four words either way: what a lane loads per round (three of them in version 2), then the four LDS
+// addresses its entries went to.
 template <int NB, int WAVES, int R, int NS, int FMT>
 __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
-  typedef typename std::conditional<FMT == 2, u32x3, u32x4>::type stage_t;  // what a lane loads per round
+  typedef u32x4 stage_t;
   constexpr uint32_t kRoundWords = FMT == 2 ? kRoundWords2 : 256u;
   extern __shared__ __align__(16) unsigned char lds[];
   const int lane = threadIdx.x & 63;
@@ -114,8 +116,9 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       if constexpr (FMT == 2) {
-        if (FLS_ABLATE & 32) s[r] = u32x3{(uint32_t)lane, 1u, 0x01010101u};
-        else s[r] = __builtin_amdgcn_raw_buffer_load_b96(rsrc, (r * 64 + lane) * 12, 0, kAuxNonTemporal);
+        u32x3 g = {(uint32_t)lane, 1u, 0x01041000u};
+        if (!(FLS_ABLATE & 32)) g = __builtin_amdgcn_raw_buffer_load_b96(rsrc, (r * 64 + lane) * 12, 0, kAuxNonTemporal);
+        s[r] = u32x4{g[0], g[1], g[2], 0u};
       } else {
         if (FLS_ABLATE & 32) s[r] = u32x4{(uint32_t)lane, 1u, 2u, 3u};
         else s[r] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (r * 64 + lane) * 16, 0, kAuxNonTemporal);
@@ -134,19 +137,13 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   auto extract = [&](stage_t(&s)[R], uint32_t begin, uint32_t end) {
     const uint32_t n = end - begin;
     if constexpr (FMT == 2) {
-      // locations are running sums of the entries' distances: a lane's group starts where the groups of
-      // the lanes (and rounds) before it end - a wave prefix sum of the groups' distance sums per round
-      uint32_t counter = 0;
 #pragma unroll
       for (int r = 0; r < R; ++r) {
-        const uint32_t sum = __builtin_amdgcn_sad_u8(s[r][2], 0u, 0u);  // the four distances added up
-        const uint32_t incl = wave_prefix_sum(sum, lane);
         // no branch: a lane past the end of the run (its loads returned 0) writes zeros to the padding slot
-        const bool mine = (r * 64 + lane) * kGroupWords < n;
-        if (!(FLS_ABLATE & 4)) extract_group(s[r], mine ? counter + incl - sum : 0u, mine ? tile_addr : tile_addr + (uint32_t)kTileBytes);
-        counter += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+        const uint32_t base = (r * 64 + lane) * kGroupWords < n ? tile_addr : tile_addr + (uint32_t)kTileBytes;
+        s[r] = extract_group(s[r][0], s[r][1], s[r][2], base, !(FLS_ABLATE & 4));
       }
-      if (n > R * kRoundWords) extract_overflow_v2(p.words, begin + R * kRoundWords, end, counter, tile);
+      if (n > R * kRoundWords) extract_overflow_v2(p.words, begin + R * kRoundWords, end, tile);
       return;
     } else {
 #pragma unroll
@@ -170,12 +167,10 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   // rst_smem for sparse tiles: instead of zeroing all 8 KB (eight 16 B stores per lane, 64 LDS
   // clocks), store a zero at the places the tile's words went to - the same count of 2 B stores
   // as the extraction, which is less LDS time as long as a tile has at most about 1000 words.
-  // (version 2 keeps no addresses: its tiles are always cleared whole)
-  constexpr bool kUnscatter = FMT == 1 && R <= 4;
+  constexpr bool kUnscatter = R <= 4;
   auto unscatter = [&](const stage_t(&s)[R], uint32_t begin, uint32_t end) {
     const uint32_t n = end - begin;
-    if constexpr (FMT == 2) {
-    } else if (n > R * 256u) {  // the overflow path wrote words this wave no longer holds
+    if (n > R * kRoundWords) {  // the overflow path wrote words this wave no longer holds
 #pragma unroll
       for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
     } else {

@@ -54,60 +54,38 @@ static __device__ __noinline__ void extract_overflow(const uint32_t* words, uint
   }
 }
 
-// ---- format version 2: groups of four entries in three words (two of values, one of 8-bit distances)
+// ---- format version 2: groups of four entries in three words (two of values, one of locations)
 
 typedef unsigned int u32x3 __attribute__((ext_vector_type(3)));
 constexpr uint32_t kGroupWords = 3;  // words of a group
 constexpr uint32_t kRoundWords2 = 64 * kGroupWords;  // words one round of 64 lanes stages (256 entries)
 
-// Inclusive prefix sum over the 64 lanes: four steps inside the rows of 16 lanes (DPP row shifts),
-// then the totals of the rows before are added through scalar registers.
-__device__ __forceinline__ uint32_t wave_prefix_sum(uint32_t v, int lane) {
-#define FLS_ROW_SHR(n) v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x110 + (n), 0xf, 0xf, true)
-  FLS_ROW_SHR(1);
-  FLS_ROW_SHR(2);
-  FLS_ROW_SHR(4);
-  FLS_ROW_SHR(8);
-#undef FLS_ROW_SHR
-  const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 15);
-  const uint32_t r1 = r0 + (uint32_t)__builtin_amdgcn_readlane((int)v, 31);
-  const uint32_t r2 = r1 + (uint32_t)__builtin_amdgcn_readlane((int)v, 47);
-  const uint32_t row = (uint32_t)lane >> 4;
-  return v + (row == 0 ? 0u : row == 1 ? r0 : row == 2 ? r1 : r2);
-}
-
-// The four entries of one group: their values go to the locations that the running counter reaches.
-// `counter` = the location counter in front of this lane's group; `base` = LDS byte address of the tile
-// (or of the padding slot, with counter 0, for a lane past the end of the run, whose loads returned 0).
-__device__ __forceinline__ void extract_group(const u32x3& g, uint32_t counter, uint32_t base) {
+// Format version 2: the four entries of one group (value0 | value1 << 16, value2 | value3 << 16, loc0 | dist1 << 12 |
+// dist2 << 18 | dist3 << 24).  The values go to their locations in the LDS tile at byte address `base` (or of the
+// padding slot, for a lane past the end of the run, whose loads returned 0); returns the four byte addresses,
+// which is all the later re-zeroing needs.  A group decodes by itself: three additions, nothing from other lanes.
+__device__ __forceinline__ u32x4 extract_group(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t base, bool store = true) {
   typedef __attribute__((address_space(3))) uint16_t* lds_u16_ptr;
-  const uint32_t l0 = counter + (g[2] & 0xffu);
-  const uint32_t l1 = l0 + ((g[2] >> 8) & 0xffu);
-  const uint32_t l2 = l1 + ((g[2] >> 16) & 0xffu);
-  const uint32_t l3 = l2 + (g[2] >> 24);
-  *(lds_u16_ptr)(uintptr_t)(base + 2u * l0) = (uint16_t)g[0];
-  *(lds_u16_ptr)(uintptr_t)(base + 2u * l1) = (uint16_t)(g[0] >> 16);
-  *(lds_u16_ptr)(uintptr_t)(base + 2u * l2) = (uint16_t)g[1];
-  *(lds_u16_ptr)(uintptr_t)(base + 2u * l3) = (uint16_t)(g[1] >> 16);
+  const uint32_t a0 = base + 2u * (w2 & 0xfffu);
+  const uint32_t a1 = a0 + 2u * ((w2 >> 12) & 0x3fu);
+  const uint32_t a2 = a1 + 2u * ((w2 >> 18) & 0x3fu);
+  const uint32_t a3 = a2 + 2u * ((w2 >> 24) & 0x3fu);
+  if (store) {  // (false in the latency-breakdown builds that erase the extraction)
+    *(lds_u16_ptr)(uintptr_t)a0 = (uint16_t)w0;
+    *(lds_u16_ptr)(uintptr_t)a1 = (uint16_t)(w0 >> 16);
+    *(lds_u16_ptr)(uintptr_t)a2 = (uint16_t)w1;
+    *(lds_u16_ptr)(uintptr_t)a3 = (uint16_t)(w1 >> 16);
+  }
+  return u32x4{a0, a1, a2, a3};
 }
 
 // Groups of a tile beyond the R rounds that the register ring stages (a tile denser than the kernel
-// variant was picked for): loaded and extracted on the spot.  `counter` = the location counter
-// behind the staged groups.  Slow, rare, and out of line.
-static __device__ __noinline__ void extract_overflow_v2(const uint32_t* words, uint32_t begin, uint32_t end, uint32_t counter,
-                                                        unsigned char* tile) {
+// variant was picked for): loaded and extracted on the spot.  Slow, rare, and out of line.
+static __device__ __noinline__ void extract_overflow_v2(const uint32_t* words, uint32_t begin, uint32_t end, unsigned char* tile) {
   const int lane = threadIdx.x & 63;
   const uint32_t tile_addr = (uint32_t)(uintptr_t)tile;
-  for (uint32_t i = begin; i < end; i += kRoundWords2) {
-    const uint32_t w = i + (uint32_t)lane * kGroupWords;
-    u32x3 g = {0u, 0u, 0u};
-    if (w < end) g = u32x3{words[w], words[w + 1], words[w + 2]};
-    const uint32_t sum = __builtin_amdgcn_sad_u8(g[2], 0u, 0u);
-    const uint32_t incl = wave_prefix_sum(sum, lane);
-    // lanes past the end hold zeros: they would write a zero where the counter stands, so they get the padding slot
-    extract_group(g, w < end ? counter + incl - sum : 0u, w < end ? tile_addr : tile_addr + (uint32_t)kTileBytes);
-    counter += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-  }
+  for (uint32_t w = begin + (uint32_t)lane * kGroupWords; w < end; w += kRoundWords2)
+    extract_group(words[w], words[w + 1], words[w + 2], tile_addr);
 }
 
 }  // namespace fls

@@ -1,4 +1,4 @@
-"""Format version 2 (8-bit location distances, 3 bytes per nonzero) on the GPU: the compressor bit for bit
+"""Format version 2 (four entries share a word of locations, 3 bytes per nonzero) on the GPU: the compressor bit for bit
 against the oracle's, and fls_spmm on version-2 blobs against the oracle's fp64 triple loop (whole C)."""
 import numpy as np
 import pytest
@@ -38,7 +38,7 @@ def _cases():
         ("half-dense", 640, 512, 0.5, "uniform"),
         ("dense-0pct", 384, 256, 0.0, "uniform"),
         ("row-skewed", 2048, 1024, 0.8, "row_skewed"),
-        # sparse enough for many gaps of more than 255 locations (bridge entries), and for empty tiles
+        # sparse enough for many gaps of more than 63 locations (bridge entries), and for empty tiles
         ("uniform-99", 1024, 512, 0.99, "uniform"),
         ("uniform-99.9", 512, 1024, 0.999, "uniform"),
         ("long-share-kt2", 128 * 700, 64, 0.8, "uniform"),
