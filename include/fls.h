@@ -122,8 +122,7 @@ int fls_compress(const void* W_dev, int64_t M, int64_t K, void* out_dev, size_t 
  *   the empty locations behind the tile's last entry, at most three past the end of the tile.
  * fls_compress_v2 is fls_compress for this format (same arguments without the order policy, same
  * errors, same waiting); fls_compress_bound_v2 its capacity bound.  fls_inspect and fls_spmm take
- * blobs of either version (fls_spmm tells them apart by the header); a version-2 blob is multiplied
- * in passes of up to 32 columns whatever N is.
+ * blobs of either version (fls_spmm tells them apart by the header) and run the same passes on both.
  */
 int fls_compress_bound_v2(int64_t M, int64_t K, size_t* bytes_host);
 int fls_compress_v2(const void* W_dev, int64_t M, int64_t K, void* out_dev, size_t out_capacity,
@@ -181,7 +180,7 @@ int fls_check_workspace(fls_stream_t stream);
  * from fls_compress is right by construction).  As a guard for blobs that were stored and read back, the
  * passes of up to 32 columns take no offset to lie beyond the header's word count, so a truncated or
  * damaged TileOffsets section gives wrong results, not loads outside NonZeros; the 64-column pass
- * (N > 32, format version 1) trusts TileOffsets.
+ * (N > 32) trusts TileOffsets.
  * Errors: FLS_EINVAL, FLS_EALIGN, FLS_EFORMAT, FLS_EWORKSPACE, FLS_EHIP.
  */
 int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int64_t K, int64_t N,

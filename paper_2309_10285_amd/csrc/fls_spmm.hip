@@ -437,11 +437,10 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
   else if (a.max_tile_words <= 3 * round_words) R = 3;
   else if (a.max_tile_words <= 4 * round_words) R = 4;
   else if (a.max_tile_words <= 6 * round_words) R = 6;
-  // The 64-column pass stages at most 2560 words of a tile (it has no slow path for more; twelve
-  // rounds of 256 no longer fit its registers): a matrix with denser tiles - less than 40 % sparse
+  // The 64-column pass stages at most ten rounds of a tile (it has no slow path for more; twelve
+  // rounds no longer fit its registers): a matrix with denser tiles - less than 40 % sparse
   // somewhere - takes 32-column passes throughout.
-  // (and so does a version-2 blob: the 64-column pass reads version 1 only)
-  const bool wide_ok = !v2 && a.max_tile_words <= 10 * 256;
+  const bool wide_ok = a.max_tile_words <= 10 * round_words;
   for (uint32_t n0 = 0; n0 < a.N;) {
     p.out.n0 = n0;
     const uint32_t left = a.N - n0;

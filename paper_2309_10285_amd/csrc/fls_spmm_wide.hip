@@ -27,6 +27,7 @@
 
 #include "fls_device.h"
 #include "fls_launch.h"
+#include "fls_tile.h"
 
 // Latency-breakdown builds (see fls_spmm.hip): 2 no MFMA, 4 no extract, 8 no re-zeroing, 16 no LDS
 // fragment reads, 32 no global loads of the words, 256 no X traffic (loads, LDS stores, B fragment
@@ -118,9 +119,12 @@ __device__ __forceinline__ void store_band32(_Float16* C, uint32_t M, uint32_t N
 template <int NS>
 constexpr int wide_lds_bytes() { return 2 * NS * 4096 + kWideWaves * kWideTileLds; }
 
-template <int R, int NS>
+// FMT = format version of the blob (see fls_spmm.hip): a stage register holds a round's four words
+// (version 1) or a group's three (version 2) and, once extracted, the four LDS addresses they went to.
+template <int R, int NS, int FMT>
 __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p) {
   constexpr int NB = kWideNB;
+  constexpr uint32_t kRoundWords = FMT == 2 ? kRoundWords2 : 256u;  // words one round of 64 lanes stages
   static_assert(NS == 4 || NS == 8, "a body is 4 or 8 tiles");
   constexpr uint32_t kChunkBytes = NS * 4096u;
   extern __shared__ __align__(16) unsigned char lds[];
@@ -248,14 +252,20 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
     const uint32_t begin = (uint32_t)__builtin_amdgcn_readlane((int)window, i);
     const uint32_t end = (uint32_t)__builtin_amdgcn_readlane((int)window, i + 1);
     n = end - begin;
-    if (n > R * 256u) n = R * 256u;
+    if (n > R * kRoundWords) n = R * kRoundWords;
     if (rel >= ntiles) n = 0;
     const __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void*)(p.words + begin), 0, (int)(n * 4u), kBufferFlags);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      if (FLS_ABLATE & 32) s[r] = u32x4{(uint32_t)lane, 1u, 2u, 3u};
-      else s[r] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (r * 64 + lane) * 16, 0, kAuxNonTemporal);
+      if constexpr (FMT == 2) {
+        u32x3 g = {(uint32_t)lane, 1u, 0x01041000u};
+        if (!(FLS_ABLATE & 32)) g = __builtin_amdgcn_raw_buffer_load_b96(rsrc, (r * 64 + lane) * 12, 0, kAuxNonTemporal);
+        s[r] = u32x4{g[0], g[1], g[2], 0u};
+      } else {
+        if (FLS_ABLATE & 32) s[r] = u32x4{(uint32_t)lane, 1u, 2u, 3u};
+        else s[r] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (r * 64 + lane) * 16, 0, kAuxNonTemporal);
+      }
     }
   };
 
@@ -268,14 +278,19 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   auto extract = [&](u32x4(&s)[R], uint32_t n) {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      const uint32_t base = (r * 64 + lane) * 4u < n ? tile_addr : tile_addr + (uint32_t)kTileBytes;
+      if constexpr (FMT == 2) {
+        const uint32_t base = (r * 64 + lane) * kGroupWords < n ? tile_addr : tile_addr + (uint32_t)kTileBytes;
+        s[r] = extract_group(s[r][0], s[r][1], s[r][2], base, !(FLS_ABLATE & 4));
+      } else {
+        const uint32_t base = (r * 64 + lane) * 4u < n ? tile_addr : tile_addr + (uint32_t)kTileBytes;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint32_t w = s[r][j];
-        const uint32_t addr = scatter_addr(w, base);
-        if (FLS_ABLATE & 4) asm volatile("" ::"v"(w));
-        else *(lds_u16_ptr)(uintptr_t)addr = (uint16_t)(w >> 16);
-        s[r][j] = addr;
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t w = s[r][j];
+          const uint32_t addr = scatter_addr(w, base);
+          if (FLS_ABLATE & 4) asm volatile("" ::"v"(w));
+          else *(lds_u16_ptr)(uintptr_t)addr = (uint16_t)(w >> 16);
+          s[r][j] = addr;
+        }
       }
     }
   };
@@ -308,7 +323,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
     constexpr int kE = 5 * R;                                   // extraction: per round a base select and four words
     constexpr int kOps = 1 + kZ + kE + 1 + kFragsA + kFragsB + 1;
     constexpr int kMfmas = kSteps16 * kRowBlocks32 * kColBlocks32;
-    uint32_t ebase = 0;
+    uint32_t ebase = 0, eaddr = 0, ekeep = 0;
     auto other = [&](auto o_) {
       constexpr int o = decltype(o_)::value;
       if constexpr (o == 0) {
@@ -329,7 +344,23 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
       } else if constexpr (o < 1 + kZ + kE) {
         constexpr int r = (o - 1 - kZ) / 5, j = (o - 1 - kZ) % 5 - 1;
         if constexpr (j < 0) {
-          ebase = (r * 64 + lane) * 4u < nn ? tile_addr : tile_addr + (uint32_t)kTileBytes;
+          ebase = (r * 64 + lane) * (FMT == 2 ? kGroupWords : 4u) < nn ? tile_addr : tile_addr + (uint32_t)kTileBytes;
+        } else if constexpr (FMT == 2) {
+          // entry j of the lane's group: its address is the one before plus a 6-bit distance (the first: the
+          // group's 12-bit location); the words make room for the addresses as they are used up
+          const uint32_t w2 = nxt[r][2];
+          if constexpr (j == 0) eaddr = ebase + 2u * (w2 & 0xfffu);
+          else eaddr = eaddr + 2u * ((w2 >> (6 + 6 * j)) & 0x3fu);
+          const uint32_t v = nxt[r][j >> 1];
+          if (FLS_ABLATE & 4) asm volatile("" ::"v"(v));
+          else *(lds_u16_ptr)(uintptr_t)eaddr = (j & 1) ? (uint16_t)(v >> 16) : (uint16_t)v;
+          if constexpr (j == 0) nxt[r][3] = eaddr;
+          else if constexpr (j == 1) nxt[r][0] = eaddr;
+          else if constexpr (j == 2) ekeep = eaddr;
+          else {
+            nxt[r][1] = ekeep;
+            nxt[r][2] = eaddr;
+          }
         } else {
           const uint32_t w = nxt[r][j];
           const uint32_t addr = scatter_addr(w, ebase);
@@ -369,10 +400,15 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   auto plain_tile = [&](uint32_t t, uint32_t kt) {
     const uint32_t begin = (uint32_t)__builtin_amdgcn_readfirstlane((int)offs[t]);
     const uint32_t end = (uint32_t)__builtin_amdgcn_readfirstlane((int)offs[t + 1]);
-    for (uint32_t i = begin + (uint32_t)lane * 4u; i < end; i += 256u) {
-      const u32x4 w = *(const u32x4*)(p.words + i);
+    if constexpr (FMT == 2) {
+      for (uint32_t i = begin + (uint32_t)lane * kGroupWords; i < end; i += kRoundWords2)
+        extract_group(p.words[i], p.words[i + 1], p.words[i + 2], tile_addr);
+    } else {
+      for (uint32_t i = begin + (uint32_t)lane * 4u; i < end; i += 256u) {
+        const u32x4 w = *(const u32x4*)(p.words + i);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) *(uint16_t*)(tile + ((w[j] & 0xffffu) << 1)) = (uint16_t)(w[j] >> 16);
+        for (int j = 0; j < 4; ++j) *(uint16_t*)(tile + ((w[j] & 0xffffu) << 1)) = (uint16_t)(w[j] >> 16);
+      }
     }
     half8 fa[kFragsA], fb[kFragsB];
 #pragma unroll
@@ -397,7 +433,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   // stage its tiles: the whole grid then takes the plain loop for all its tiles, which is slow and right.
   const uint32_t densest = offs[kHeaderMaxTileWords - kHeaderWords];
   uint32_t kplain = k0;  // first K tile of the plain loop
-  if (densest <= R * 256u && bodies > 0) {
+  if (densest <= R * kRoundWords && bodies > 0) {
     kplain = k1;
     // Prologue: the first chunk of X into LDS, the ring of words filled, the first tile in LDS and
     // its fragments in registers.  (The next window of offsets is requested before the ring's loads,
@@ -504,19 +540,19 @@ __global__ __launch_bounds__(256) void wide_reduce_kernel(WideParams p) {
   }
 }
 
-template <int R, int NS>
+template <int R, int NS, int FMT>
 static hipError_t launch_wide_variant(WideParams p, int cus, hipStream_t stream) {
   static std::atomic<bool> attr_done{false};  // per kernel variant; setting the attribute twice from two threads is harmless
   constexpr int kLds = wide_lds_bytes<NS>();
   if (!attr_done.load(std::memory_order_acquire)) {
-    hipError_t e = hipFuncSetAttribute((const void*)spmm_wide_kernel<R, NS>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+    hipError_t e = hipFuncSetAttribute((const void*)spmm_wide_kernel<R, NS, FMT>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
     if (e != hipSuccess) return e;
     attr_done.store(true, std::memory_order_release);
   }
   const uint32_t quads = (p.bands + 3u) / 4u;
   p.S = wide_quad_slices(p.bands, p.G, p.KT, cus, NS);
   const uint32_t grid = (quads * p.S + 7u) / 8u * 8u * p.G;  // (group of bands, slice) pairs rounded up to eight, x column groups
-  hipLaunchKernelGGL((spmm_wide_kernel<R, NS>), dim3(grid), dim3(kWideWaves * 64), kLds, stream, p);
+  hipLaunchKernelGGL((spmm_wide_kernel<R, NS, FMT>), dim3(grid), dim3(kWideWaves * 64), kLds, stream, p);
   hipError_t e = hipGetLastError();
   if (e == hipSuccess && p.S > 1) e = launch_wide_reduce(p, true, stream);
   return e;
@@ -554,13 +590,23 @@ hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, uint32_t groups, h
   p.KT = a.K / kTileK;
   p.bands = a.M / kTileM;
   p.S = 1;
-  // rounds of 256 words staged per tile; the ring is 8 tiles deep while the registers allow
-  if (a.max_tile_words <= 2 * 256) return launch_wide_variant<2, 8>(p, a.num_cus, stream);
-  if (a.max_tile_words <= 3 * 256) return launch_wide_variant<3, 8>(p, a.num_cus, stream);
-  if (a.max_tile_words <= 4 * 256) return launch_wide_variant<4, 8>(p, a.num_cus, stream);
-  if (a.max_tile_words <= 6 * 256) return launch_wide_variant<6, 4>(p, a.num_cus, stream);
-  if (a.max_tile_words <= 8 * 256) return launch_wide_variant<8, 4>(p, a.num_cus, stream);
-  return launch_wide_variant<10, 4>(p, a.num_cus, stream);
+  // rounds staged per tile (256 words in version 1, 64 groups = 192 words in version 2); the ring is 8 tiles
+  // deep while the registers allow
+  if (a.version == 2) {
+    const uint32_t round = kRoundWords2;
+    if (a.max_tile_words <= 2 * round) return launch_wide_variant<2, 8, 2>(p, a.num_cus, stream);
+    if (a.max_tile_words <= 3 * round) return launch_wide_variant<3, 8, 2>(p, a.num_cus, stream);
+    if (a.max_tile_words <= 4 * round) return launch_wide_variant<4, 8, 2>(p, a.num_cus, stream);
+    if (a.max_tile_words <= 6 * round) return launch_wide_variant<6, 4, 2>(p, a.num_cus, stream);
+    if (a.max_tile_words <= 8 * round) return launch_wide_variant<8, 4, 2>(p, a.num_cus, stream);
+    return launch_wide_variant<10, 4, 2>(p, a.num_cus, stream);
+  }
+  if (a.max_tile_words <= 2 * 256) return launch_wide_variant<2, 8, 1>(p, a.num_cus, stream);
+  if (a.max_tile_words <= 3 * 256) return launch_wide_variant<3, 8, 1>(p, a.num_cus, stream);
+  if (a.max_tile_words <= 4 * 256) return launch_wide_variant<4, 8, 1>(p, a.num_cus, stream);
+  if (a.max_tile_words <= 6 * 256) return launch_wide_variant<6, 4, 1>(p, a.num_cus, stream);
+  if (a.max_tile_words <= 8 * 256) return launch_wide_variant<8, 4, 1>(p, a.num_cus, stream);
+  return launch_wide_variant<10, 4, 1>(p, a.num_cus, stream);
 }
 
 }  // namespace fls

@@ -134,7 +134,7 @@ def test_spmm_v2_small_integers_exact_and_identity(fls, oracle_mod):
     assert np.array_equal(C2.view(np.uint16), W2.T)
 
 
-@pytest.mark.parametrize("name", ["C2", "C3"])
+@pytest.mark.parametrize("name", ["C2", "C3", "C4"])
 def test_named_configuration_v2_whole_c_and_blob(fls, oracle_mod, name):
     cfg = wl.CONFIGS[name]
     W, X = wl.make_inputs(cfg)
@@ -151,13 +151,14 @@ def test_named_configuration_v2_whole_c_and_blob(fls, oracle_mod, name):
     assert float(np.abs(C.astype(np.float64) - ref).max()) / float(np.abs(ref).max()) <= TOL
 
 
-def test_v2_blob_replaced_in_place_by_a_denser_one(fls, oracle_mod):
+@pytest.mark.parametrize("N", [16, 64])
+def test_v2_blob_replaced_in_place_by_a_denser_one(fls, oracle_mod, N):
     """The kernel variant is picked for a sparse blob, then a denser version-2 blob of the same shape is copied
-    over it without fls_forget: its tiles have more groups than the ring stages and the rest goes through the
-    slow path, which must carry the location counter on."""
+    over it without fls_forget: its tiles have more groups than the ring stages, and the rest goes through the
+    slow path (N = 16) or the whole grid takes the plain tile-by-tile path (N = 64)."""
     import torch
 
-    M, K, N = 1024, 2048, 16
+    M, K = 1024, 2048
     W32 = wl.gen_weights_f32(M, K, 41)
     sparse, dense = wl.prune_uniform(W32, 0.9, 42), wl.prune_uniform(W32, 0.45, 43)
     X = wl.gen_x(N, K, 44)
