@@ -115,7 +115,7 @@ def run_sweep(args):
             cfg = wl.sweep_config(beta, mask, 8)
             Wb = (wl.prune_uniform if mask == "uniform" else wl.prune_row_skewed)(W32, beta, wl.SWEEP_SEED + 1)
             W = torch.from_numpy(Wb.view(np.float16)).cuda()
-            blob0, st = fls.fls_compress(W)
+            blob0, st = (fls.fls_compress_v2 if args.format == 2 else fls.fls_compress)(W)
             blob0 = blob0.clone()
             del W
             n_copies = max(2, -(-MIN_ROTATION_BYTES // st["bytes_total"]))
@@ -127,7 +127,7 @@ def run_sweep(args):
                 err = float(np.abs(C.cpu().numpy().astype(np.float64) - ref).max() / np.abs(ref).max())
                 alg = st["bytes_total"] + 2 * K * N + 2 * M * N
                 emit({"point": f"{mask}-{int(round(beta * 100))}-N{N}", "mask": mask, "sparsity": beta, "N": N,
-                      "nnz": st["nnz"], "max_tile_words": st["max_tile_words"], "us": round(ms * 1e3, 2),
+                      "format": args.format, "nnz": st["nnz"], "max_tile_words": st["max_tile_words"], "us": round(ms * 1e3, 2),
                       "TFLOPs": round(2.0 * M * K * N / ms / 1e9, 1), "GBps": round(alg / ms / 1e6, 1),
                       "hbm_frac": round(alg / ms / 1e6 / HBM_PEAK_GBS, 4), "speedup_vs_dense": round(dense_ms[N] / ms, 3),
                       "max_rel_err_whole_c": err, "parity_ok": err <= 2e-3})
@@ -452,6 +452,8 @@ def main():
     ap.add_argument("--no-others", action="store_true",
                     help="leave out the other named configurations (C2, C3) that the default run reports beside the headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--format", type=int, choices=(1, 2), default=1,
+                    help="--sweep only: the blob format of the sweep's sparse points (1: the paper's word; 2: three bytes per nonzero)")
     ap.add_argument("--no-v2", dest="v2", action="store_false",
                     help="leave out the run of the same matrix in format version 2 (3 bytes per nonzero)")
     ap.add_argument("--no-dense", action="store_true")
