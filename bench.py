@@ -37,7 +37,7 @@ OTHERS = ("C2", "C3")   # reported beside it in the same JSON line
 # under profiles/; the line carries the figure together with the file it was copied from, or null.
 MEASURED_TRAFFIC = {
     "C2": (169.90e6, "profiles/spmm_C2_hbm_traffic.md (separate rocprofv3 --pmc runs, not this run)"),
-    "C4": (336.16e6, "profiles/spmm_C4_hbm_traffic.md (separate rocprofv3 --pmc runs, not this run; both kernels of the call)"),
+    "C4": (335.87e6, "profiles/spmm_C4_hbm_traffic.md (separate rocprofv3 --pmc runs, not this run; both kernels of the call)"),
 }
 
 
@@ -306,6 +306,8 @@ def measure_config(name, args, with_dense, with_cpu):
     t_gen = time.perf_counter()
     W32 = wl.make_w32(cfg)
     Wb, Xb = wl.make_inputs(cfg, W32)
+    if args.x_values != "workload":  # same shapes, same instruction stream: only the operand values differ
+        Xb = np.full_like(Xb, 0x3C00 if args.x_values == "ones" else 0)
     t_gen = time.perf_counter() - t_gen
 
     X = torch.from_numpy(Xb.view(np.float16)).cuda()
@@ -417,7 +419,7 @@ def measure_config(name, args, with_dense, with_cpu):
             for _ in range(reps):
                 ref = oracle.ref_spmm_f64(Wb, Xb)
             dt = (time.perf_counter() - t0) / reps
-        scale = float(np.abs(ref).max())
+        scale = max(float(np.abs(ref).max()), 1e-30)
         err = float(np.abs(C_host.astype(np.float64) - ref).max()) / scale
         res["cpu_baseline"] = {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s",
                                "cores": oracle.ref_threads(), "kind": "oracle",
@@ -467,6 +469,9 @@ def main():
                     help="instead of the bench line: the four MatMuls of one OPT-30B-shaped decoder layer back to back, "
                          "eager and as a HIP graph")
     ap.add_argument("--layer-n", type=int, default=16, help="with --layer: the batch size N")
+    ap.add_argument("--x-values", choices=("workload", "zeros", "ones"), default="workload",
+                    help="a study, not the benchmark: X of the workload's shape filled with zeros or ones (how much of a "
+                         "call's time depends on the operand values, i.e. on power; the line is marked)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (the known-size kernel the HBM counters "
                          "of a rocprofv3 --pmc run are scaled by)")
@@ -508,6 +513,9 @@ def main():
     for key in ("format_v2", "dense_gemm", "vendor_gemm", "cpu_baseline", "parity"):
         if key in r:
             out[key] = r[key]
+    if args.x_values != "workload":
+        out["data"] = f"synthetic; NOT the workload's X: X filled with {args.x_values} (operand-value study)"
+        out["config"]["x_values"] = args.x_values
     gen_s = r["t_gen"]
     failed = [args.config] if "parity" in r and not r["parity"]["ok"] else []
 

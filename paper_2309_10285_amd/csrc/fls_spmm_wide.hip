@@ -84,6 +84,12 @@ __device__ __forceinline__ void static_for(F&& f) {
 // of the 32x32x16 shape, lane l = 32 h + c:
 //   A: row c of the 32-row block, the 8 k of chunk h of the 16-k step;  B: column c, the same 8 k;
 //   C/D: column c, rows 8 q + 4 h + (0..3) in registers 4 q .. 4 q + 3, q = 0..3.
+// A and B hold the same thing in the same lanes, so either operand can be the W block.  The pass
+// computes the transposed product, X block (A) times W block (B): the chip's clock under this
+// kernel is set by power, the matrix cores draw less when the operand that is mostly zeros is B,
+// and the call is 3 % faster for it (measured; with X all zeros instead of random values the same
+// instruction stream runs 18 % faster still, with W's values all equal 2 %).  An accumulator block
+// is therefore 32 columns of X (its rows) by 32 rows of W (its columns).
 typedef float float16v __attribute__((ext_vector_type(16)));
 __device__ __forceinline__ void mfma_in_place(float16v& acc, const half8& a, const half8& b) {
   asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
@@ -92,25 +98,25 @@ constexpr int kRowBlocks32 = kTileM / 32;  // 32-row blocks of a tile
 constexpr int kColBlocks32 = 2;            // 32-column blocks of a pass
 constexpr int kSteps16 = kTileK / 16;      // 16-k steps of a tile
 
-// Converts a wave's 128 x 64 accumulators (32x32 layout) to fp16 and stores them to column-major C.
+// Converts a wave's 128 x 64 accumulators (32x32 layout, transposed: see above) to fp16 and stores them
+// to column-major C: register 4 q + r of block (rb, cb) is row 32 rb + c of the band, column
+// 32 cb + 8 q + 4 h + r of the group - 64 contiguous bytes of C per store and half wave.
 __device__ __forceinline__ void store_band32(_Float16* C, uint32_t M, uint32_t N, uint32_t n0,
                                              const float16v (&acc)[kRowBlocks32][kColBlocks32], uint32_t band, int lane) {
   const uint32_t c = lane & 31, h = lane >> 5;
 #pragma unroll
-  for (int cb = 0; cb < kColBlocks32; ++cb) {
-    const uint32_t n = n0 + cb * 32 + c;
-    if (n < N) {
+  for (int cb = 0; cb < kColBlocks32; ++cb)
 #pragma unroll
-      for (int rb = 0; rb < kRowBlocks32; ++rb)
+    for (int q = 0; q < 4; ++q)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          half4 v;
+      for (int r = 0; r < 4; ++r) {
+        const uint32_t n = n0 + cb * 32 + q * 8 + h * 4 + r;
+        if (n < N) {
 #pragma unroll
-          for (int r = 0; r < 4; ++r) v[r] = (_Float16)acc[rb][cb][4 * q + r];
-          *(half4*)(C + (size_t)n * M + band * kTileM + rb * 32 + q * 8 + h * 4) = v;
+          for (int rb = 0; rb < kRowBlocks32; ++rb)
+            C[(size_t)n * M + band * kTileM + rb * 32 + c] = (_Float16)acc[rb][cb][4 * q + r];
         }
-    }
-  }
+      }
 }
 
 // LDS of a workgroup: two X chunks (a chunk = the NS K tiles of a loop body x 64 columns, 4 KB per
@@ -388,7 +394,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
       constexpr int s = decltype(s_)::value;
       constexpr int ks = s / (kRowBlocks32 * kColBlocks32), rb = (s / kColBlocks32) % kRowBlocks32, cb = s % kColBlocks32;
       if (FLS_ABLATE & 2) acc[rb][cb][0] += (float)fa[ks * kRowBlocks32 + rb][0] * (float)fb[ks * kColBlocks32 + cb][0];
-      else mfma_in_place(acc[rb][cb], fa[ks * kRowBlocks32 + rb], fb[ks * kColBlocks32 + cb]);
+      else mfma_in_place(acc[rb][cb], fb[ks * kColBlocks32 + cb], fa[ks * kRowBlocks32 + rb]);
       static_for<s * kOps / kMfmas, (s + 1) * kOps / kMfmas>(other);
     });
   };
@@ -425,7 +431,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
       for (int rb = 0; rb < kRowBlocks32; ++rb)
 #pragma unroll
         for (int cb = 0; cb < kColBlocks32; ++cb)
-          acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ks * kRowBlocks32 + rb], fb[ks * kColBlocks32 + cb], acc[rb][cb], 0, 0, 0);
+          acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[ks * kColBlocks32 + cb], fa[ks * kRowBlocks32 + rb], acc[rb][cb], 0, 0, 0);
   };
 
   // The launcher picks R from the header the host remembers for this blob address.  If the memory
@@ -487,7 +493,8 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   if (p.S == 1) {
     store_band32(p.C, p.M, p.N, n0, acc, band, lane);
   } else {
-    // [band][column group][slice][column block][row block][q][lane] float4: rows 8 q + 4 (lane >> 5) + (0..3) of the row block
+    // [band][column group][slice][column block][row block][q][lane] float4: row (lane & 31) of the row block,
+    // columns 8 q + 4 (lane >> 5) + (0..3) of the column block
     float4v* dst = (float4v*)p.parts + ((size_t)((band * p.G + cg) * p.S + slice) * (NB * kRowBlocks)) * 64 + lane;
 #pragma unroll
     for (int cb = 0; cb < kColBlocks32; ++cb)
@@ -524,19 +531,22 @@ __global__ __launch_bounds__(256) void wide_reduce_kernel(WideParams p) {
     for (int j = 0; j < 8; ++j)
       if (s0 + j < p.S) sum += v[j];
   }
-  uint32_t n, row;
   if (LAYOUT32) {
-    n = n0 + (sub / 16u) * 32u + (lane & 31u);
-    row = ((sub / 4u) % 4u) * 32u + (sub % 4u) * 8u + (lane >> 5) * 4u;
-  } else {
-    n = n0 + (sub / kRowBlocks) * 16u + (lane & 15u);
-    row = (sub % kRowBlocks) * 16u + (lane >> 4) * 4u;
-  }
-  if (n < p.N) {
-    half4 h;
+    // four columns of one row per lane: 64 contiguous bytes of C per store and half wave
+    const uint32_t n = n0 + (sub / 16u) * 32u + (sub % 4u) * 8u + (lane >> 5) * 4u;
+    const uint32_t row = ((sub / 4u) % 4u) * 32u + (lane & 31u);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) h[r] = (_Float16)sum[r];
-    *(half4*)(p.C + (size_t)n * p.M + band * kTileM + row) = h;
+    for (uint32_t r = 0; r < 4; ++r)
+      if (n + r < p.N) p.C[(size_t)(n + r) * p.M + band * kTileM + row] = (_Float16)sum[r];
+  } else {
+    const uint32_t n = n0 + (sub / kRowBlocks) * 16u + (lane & 15u);
+    const uint32_t row = (sub % kRowBlocks) * 16u + (lane >> 4) * 4u;
+    if (n < p.N) {
+      half4 h;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) h[r] = (_Float16)sum[r];
+      *(half4*)(p.C + (size_t)n * p.M + band * kTileM + row) = h;
+    }
   }
 }
 
