@@ -88,7 +88,7 @@ __device__ __forceinline__ void static_for(F&& f) {
 // computes the transposed product, X block (A) times W block (B): the chip's clock under this
 // kernel is set by power, the matrix cores draw less when the operand that is mostly zeros is B,
 // and the call is 3 % faster for it (measured; with X all zeros instead of random values the same
-// instruction stream runs 18 % faster still, with W's values all equal 2 %).  An accumulator block
+// instruction stream runs 15 - 18 % faster still, with W's values all equal 2 %).  An accumulator block
 // is therefore 32 columns of X (its rows) by 32 rows of W (its columns).
 typedef float float16v __attribute__((ext_vector_type(16)));
 __device__ __forceinline__ void mfma_in_place(float16v& acc, const half8& a, const half8& b) {
