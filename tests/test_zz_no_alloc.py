@@ -60,3 +60,32 @@ def test_noalloc_entry_point_matches_fls_spmm_twice_in_a_row(oracle_mod):
         assert L.fls_spmm_noalloc(ctypes.c_void_p(blob.data_ptr()), ctypes.byref(bad), ctypes.c_void_p(X.data_ptr()),
                                   ctypes.c_void_p(got.data_ptr()), M, K, N, stream) == fls.EFORMAT
         fls.fls_forget(blob)
+
+
+def test_noalloc_entry_point_reads_format_version_2(oracle_mod):
+    """The same entry point on a version-2 blob (the statistics name the version): split bands, N = 16."""
+    import torch
+
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2309_10285_amd as fls
+
+    L = fls.lib()
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    M, K, N = 1280, 2048, 16
+    W = wl.prune_uniform(wl.gen_weights_f32(M, K, 921), 0.8, 922)
+    Xb = wl.gen_x(N, K, 923)
+    X = torch.from_numpy(Xb.view(np.float16)).cuda()
+    blob, stats = fls.fls_compress_v2(torch.from_numpy(W.view(np.float16)).cuda())
+    assert stats["format_version"] == 2
+    st = fls.FlsStats(**{k: stats[k] for k, _ in fls.FlsStats._fields_})
+    got = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+    rc = L.fls_spmm_noalloc(ctypes.c_void_p(blob.data_ptr()), ctypes.byref(st), ctypes.c_void_p(X.data_ptr()),
+                            ctypes.c_void_p(got.data_ptr()), M, K, N, stream)
+    assert rc == fls.OK
+    torch.cuda.synchronize()
+    fls.fls_check_workspace()
+    got_h = got.cpu().numpy()
+    assert not np.isnan(got_h).any()
+    ref = oracle_mod.ref_spmm_f64(W, Xb)
+    assert float(np.abs(got_h.astype(np.float64) - ref).max()) / float(np.abs(ref).max()) <= TOL
