@@ -296,7 +296,9 @@ __global__ __launch_bounds__(WAVES * 64) void spmm_kernel(SpmmParams p) {
   //    sums are there;
   //  - else: stored to the workgroup's partial-sum slot by the wave that summed them; wave 0 starts
   //    the release once all eight parts have reached the L2, and publishes the slot after the loop.
-  const bool one_band = share0 / KT == (share1 - 1) / KT && share1 - share0 >= (uint32_t)WAVES;
+  // (A build that erases the hand-over erases it in every workgroup: were this path left in, its owners would wait
+  // out their bounded spin for partial sums that the erased path never publishes.)
+  const bool one_band = !(FLS_ABLATE & (1 | 128)) && share0 / KT == (share1 - 1) / KT && share1 - share0 >= (uint32_t)WAVES;
   auto one_band_sum = [&](uint32_t band) {
     static_assert(WAVES == kRowBlocks, "one row block per wave");
     const bool from_start = share0 % KT == 0, to_end = share1 % KT == 0;
