@@ -320,7 +320,11 @@ def measure_config(name, args, with_dense, with_cpu):
     fls.ensure_workspace(M, K, N)
     C = torch.empty((N, M), dtype=torch.float16, device="cuda")
 
-    ms, host_ms = _time_loop([fls.prepare_spmm(b, X, C, M, K, N) for b in blobs], args.steps, args.warmup)
+    if args.entry == "noalloc":  # the entry point on the library's static scratch: always the narrow kernel, N <= 32
+        calls = [fls.prepare_spmm_noalloc(b, st, X, C, M, K, N) for b in blobs]
+    else:
+        calls = [fls.prepare_spmm(b, X, C, M, K, N) for b in blobs]
+    ms, host_ms = _time_loop(calls, args.steps, args.warmup)
     flops = 2.0 * M * K * N
     alg_bytes = st["bytes_total"] + 2 * K * N + 2 * M * N  # blob + X + C
     tflops = flops / (ms * 1e-3) / 1e12
@@ -331,7 +335,10 @@ def measure_config(name, args, with_dense, with_cpu):
     # which roof: the larger of the two lower bounds on the time of a call
     t_hbm_us = alg_bytes / (HBM_PEAK_GBS * 1e3)
     t_mfma_us = flops / (MFMA_F16_PEAK_TFLOPS * 1e6)
-    narrow = N <= 32 or st["max_tile_words"] > 2560
+    # which kernels the call runs (a label; the library decides): the 64-column pass for more than 32 columns, and for
+    # 17 - 32 columns on sparse tiles and long bands (the rule of wide32_pays in csrc/fls_launch.h)
+    pass32 = 16 < N <= 32 and st["max_tile_words"] <= 1024 and K // 32 >= 384 and args.entry != "noalloc"
+    narrow = (N <= 32 and not pass32) or st["max_tile_words"] > 2560
     kernels = "fls::spmm_kernel" if narrow else "fls::spmm_wide_kernel + fls::wide_reduce_kernel"
     traffic = MEASURED_TRAFFIC.get(name)
     res = {
@@ -358,7 +365,11 @@ def measure_config(name, args, with_dense, with_cpu):
         del W2
         blobs2 = [b2] + [b2.clone() for _ in range(max(2, -(-MIN_ROTATION_BYTES // st2["bytes_total"])) - 1)]
         C2 = torch.empty((N, M), dtype=torch.float16, device="cuda")
-        ms2, _ = _time_loop([fls.prepare_spmm(b, X, C2, M, K, N) for b in blobs2], args.steps, args.warmup)
+        if args.entry == "noalloc":
+            calls2 = [fls.prepare_spmm_noalloc(b, st2, X, C2, M, K, N) for b in blobs2]
+        else:
+            calls2 = [fls.prepare_spmm(b, X, C2, M, K, N) for b in blobs2]
+        ms2, _ = _time_loop(calls2, args.steps, args.warmup)
         alg2 = st2["bytes_total"] + 2 * K * N + 2 * M * N
         res["format_v2"] = {"blob_bytes": st2["bytes_total"], "bytes_per_nnz": round(st2["bytes_nonzeros"] / max(st2["nnz"], 1), 3),
                             "ms_per_step": round(ms2, 5), "achieved_GBps_on_its_bytes": round(alg2 / ms2 / 1e6, 1),
@@ -469,6 +480,9 @@ def main():
                     help="instead of the bench line: the four MatMuls of one OPT-30B-shaped decoder layer back to back, "
                          "eager and as a HIP graph")
     ap.add_argument("--layer-n", type=int, default=16, help="with --layer: the batch size N")
+    ap.add_argument("--entry", choices=("spmm", "noalloc"), default="spmm",
+                    help="the entry point that is timed: fls_spmm, or fls_spmm_noalloc (N <= 32; it keeps to the narrow "
+                         "kernel and clears its flags with a small kernel of its own before every call; the line is marked)")
     ap.add_argument("--x-values", choices=("workload", "zeros", "ones"), default="workload",
                     help="a study, not the benchmark: X of the workload's shape filled with zeros or ones (how much of a "
                          "call's time depends on the operand values, i.e. on power; the line is marked)")
@@ -513,6 +527,8 @@ def main():
     for key in ("format_v2", "dense_gemm", "vendor_gemm", "cpu_baseline", "parity"):
         if key in r:
             out[key] = r[key]
+    if args.entry != "spmm":
+        out["config"]["entry"] = "fls_spmm_noalloc"
     if args.x_values != "workload":
         out["data"] = f"synthetic; NOT the workload's X: X filled with {args.x_values} (operand-value study)"
         out["config"]["x_values"] = args.x_values

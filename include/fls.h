@@ -134,9 +134,10 @@ int fls_inspect(const void* header_host, fls_stats* stats_host);
 
 /*
  * Bytes of device workspace fls_spmm / fls_dense_gemm need for this shape: a 4 MiB control area
- * (per-workgroup flags of the split-K hand-over, an error word), the fp32 partial sums (2 - 4 MiB
- * for N <= 32, 64 MiB for N > 32) and, for N > 32, K x N x 2 bytes for X repacked into MFMA
- * fragment order.  Returns 0 on invalid arguments.
+ * (per-workgroup flags of the split-K hand-over, an error word), the fp32 partial sums (4 MiB
+ * for N <= 16, 64 MiB above: from 17 columns on a call may take the 64-column pass, which keeps
+ * one partial result per band and K slice) and, for N > 32, K x N x 2 bytes for X repacked into
+ * MFMA fragment order.  Returns 0 on invalid arguments.
  */
 size_t fls_workspace_bytes(int64_t M, int64_t K, int64_t N);
 
@@ -180,7 +181,8 @@ int fls_check_workspace(fls_stream_t stream);
  * from fls_compress is right by construction).  As a guard for blobs that were stored and read back, the
  * passes of up to 32 columns take no offset to lie beyond the header's word count, so a truncated or
  * damaged TileOffsets section gives wrong results, not loads outside NonZeros; the 64-column pass
- * (N > 32) trusts TileOffsets.
+ * (N > 32, and calls of 17 - 32 columns on long bands of sparse tiles, where sharing X between
+ * bands makes it the faster one) trusts TileOffsets.
  * Errors: FLS_EINVAL, FLS_EALIGN, FLS_EFORMAT, FLS_EWORKSPACE, FLS_EHIP.
  */
 int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int64_t K, int64_t N,
@@ -200,8 +202,8 @@ int fls_spmm_stats(const void* Wc_dev, const fls_stats* stats_host, const void* 
 
 /*
  * fls_spmm for callers that cannot allocate device memory or wait on a stream: code under HIP graph
- * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and results as
- * fls_spmm, but
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same results as fls_spmm, always
+ * through the kernel of up to 32 columns per pass, but
  *   - the split-K scratch (hand-over flags, error word, fp32 partial sums) is a static device array
  *     inside the library, FLS_NOALLOC_SCRATCH_BYTES large, present on every GPU the library runs on
  *     from load time to the end of the process: no workspace has to be registered, and none is used;

@@ -235,6 +235,27 @@ def prepare_spmm(blob, X, C, M, K, N):
     return call
 
 
+def prepare_spmm_noalloc(blob, stats, X, C, M, K, N):
+    """As prepare_spmm, for fls_spmm_noalloc (stats: the dict fls_compress or fls_inspect returned for this blob)."""
+    import torch
+
+    assert blob.is_cuda and blob.dtype == torch.uint8 and blob.is_contiguous()
+    assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and tuple(X.shape) == (N, K)
+    assert C.is_cuda and C.dtype == torch.float16 and C.is_contiguous() and tuple(C.shape) == (N, M)
+    f = lib().fls_spmm_noalloc
+    st = FlsStats(**{k: stats[k] for k, _ in FlsStats._fields_})
+    args = (ctypes.c_void_p(blob.data_ptr()), ctypes.byref(st), ctypes.c_void_p(X.data_ptr()),
+            ctypes.c_void_p(C.data_ptr()), M, K, N, _stream())
+    keep = (blob, X, C, st)
+
+    def call(_keep=keep):
+        rc = f(*args)
+        if rc != OK:
+            _check(rc, "fls_spmm_noalloc")
+
+    return call
+
+
 def prepare_dense_gemm(W, X, C, M, K, N):
     """As prepare_spmm, for fls_dense_gemm."""
     import torch

@@ -339,6 +339,7 @@ int fls_spmm(const void* Wc_dev, const void* X_dev, void* C_dev, int64_t M, int6
   a.max_tile_words = info.max_tile_words;
   a.version = info.version;
   a.num_cus = cus;
+  a.wide32 = true;
   return fls::launch_spmm(a, (hipStream_t)stream) == hipSuccess ? FLS_OK : FLS_EHIP;
 }
 
@@ -379,6 +380,7 @@ int fls_spmm_stats(const void* Wc_dev, const fls_stats* stats_host, const void* 
   a.max_tile_words = (uint32_t)stats_host->max_tile_words;
   a.version = stats_host->format_version;
   a.num_cus = cus;
+  a.wide32 = true;
   return fls::launch_spmm(a, (hipStream_t)stream) == hipSuccess ? FLS_OK : FLS_EHIP;
 }
 
@@ -412,6 +414,7 @@ int fls_spmm_noalloc(const void* Wc_dev, const fls_stats* stats_host, const void
   a.max_tile_words = (uint32_t)stats_host->max_tile_words;
   a.version = stats_host->format_version;
   a.num_cus = cus;
+  a.wide32 = false;  // the static array has the narrow kernel's partial sums only
   return fls::launch_spmm(a, s) == hipSuccess ? FLS_OK : FLS_EHIP;
 }
 

@@ -275,6 +275,7 @@ __global__ __launch_bounds__(256) void dense_wide_kernel(WideParams p) {
 // `col_groups` groups of 64 columns from column n0 on, in one launch (the last group may reach past N)
 static hipError_t launch_dense_wide(const DenseLaunch& a, uint32_t n0, uint32_t col_groups, hipStream_t stream) {
   WideParams p;
+  p.cb = 2;
   p.offs = nullptr;
   p.words = nullptr;
   p.W = a.W;

@@ -17,6 +17,9 @@ struct SpmmLaunch {
   uint32_t max_tile_words;
   uint32_t version;  // format version of the blob (1 or 2)
   int num_cus;
+  // the partial-sum area was sized by parts_floats(N): a call of 17 - 32 columns may take the 64-column pass
+  // (false for the static scratch of the entry point that allocates nothing, which has the narrow kernel's area only)
+  bool wide32;
 };
 
 struct DenseLaunch {
@@ -72,8 +75,22 @@ inline uint32_t wide_quad_slices(uint32_t bands, uint32_t col_groups, uint32_t K
 // fp32 values of the split-K partial sums: [workgroup][column blocks][128 x 16] for the passes of
 // up to 32 columns, [band][slice][4][128 x 16] for the 64-column pass
 inline size_t parts_floats(uint32_t N) {
-  if (N > kGroupCols) return (size_t)4 * kMaxWorkgroups * 4 * 2048;
+  // (from 17 columns on: a call of 17 - 32 columns takes the 64-column pass where that is faster, see wide32_pays)
+  if (N > 16u) return (size_t)4 * kMaxWorkgroups * 4 * 2048;
   return (size_t)kMaxWorkgroups * group_blocks(N) * 2048;
+}
+
+// A call (or the rest of a call) of 17 - 32 columns: the narrow kernel with two column blocks per wave, or the
+// 64-column pass multiplying only its first 32-column block.  Every tile asks for 2 KB of X here, more than a
+// sparse tile's words, and the narrow kernel's waves fetch X from L2 each for themselves; the pass shares X between
+// four bands through LDS.  Measured (us, narrow / pass): 12288 x 49152 at 90 % 73.7 / 63.2, at 80 % 105.0 / 93.7;
+// 49152 x 12288 74.3 / 70.0 and 104.6 / 101.7; 12288 x 12288 28.2 / 27.3 and 37.0 / 35.3; but 28672 x 7168
+// 28.7 / 31.4 and 40.3 / 41.6, 7168 x 7168 16.0 / 19.0: the pass pays its second kernel and needs long bands.
+// So: tiles of up to four rounds (the variants built for one column block) and at least 384 K tiles per band.
+// In format version 2 the narrow kernel has a quarter fewer bytes to wait for and stays ahead longer (12288 x
+// 12288: 32.9 / 34.7 at 80 %, 26.2 / 27.2 at 90 %; 12288 x 49152 at 90 %: 65.6 / 62.7): from 1024 K tiles on.
+inline bool wide32_pays(uint32_t max_tile_words, uint32_t round_words, uint32_t KT, uint32_t version) {
+  return max_tile_words <= 4u * round_words && KT >= (version == 2u ? 1024u : 384u);
 }
 
 // Workspace bytes for X repacked into MFMA fragment order, [K tile][column block][lane][8 halves]
@@ -120,6 +137,7 @@ struct WideParams {
   float* parts;           // [band][slice][column block][row block][lane] float4, used when S > 1
   uint32_t M, K, N, n0, KT, bands, S;
   uint32_t G;  // groups of 64 columns in the launch, from column n0 on (sparse pass; 1 in the dense pass)
+  uint32_t cb; // 32-column blocks of a group that are multiplied and hold sums (sparse pass: 2, or 1 for a call of at most 32 columns)
 };
 
 hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream);

@@ -95,17 +95,18 @@ __device__ __forceinline__ void mfma_in_place(float16v& acc, const half8& a, con
   asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 constexpr int kRowBlocks32 = kTileM / 32;  // 32-row blocks of a tile
-constexpr int kColBlocks32 = 2;            // 32-column blocks of a pass
+constexpr int kColBlocks32 = 2;            // 32-column blocks of a group of 64 columns
 constexpr int kSteps16 = kTileK / 16;      // 16-k steps of a tile
 
 // Converts a wave's 128 x 64 accumulators (32x32 layout, transposed: see above) to fp16 and stores them
 // to column-major C: register 4 q + r of block (rb, cb) is row 32 rb + c of the band, column
 // 32 cb + 8 q + 4 h + r of the group - 64 contiguous bytes of C per store and half wave.
+template <int CB>
 __device__ __forceinline__ void store_band32(_Float16* C, uint32_t M, uint32_t N, uint32_t n0,
-                                             const float16v (&acc)[kRowBlocks32][kColBlocks32], uint32_t band, int lane) {
+                                             const float16v (&acc)[kRowBlocks32][CB], uint32_t band, int lane) {
   const uint32_t c = lane & 31, h = lane >> 5;
 #pragma unroll
-  for (int cb = 0; cb < kColBlocks32; ++cb)
+  for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
     for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -127,11 +128,16 @@ constexpr int wide_lds_bytes() { return 2 * NS * 4096 + kWideWaves * kWideTileLd
 
 // FMT = format version of the blob (see fls_spmm.hip): a stage register holds a round's four words
 // (version 1) or a group's three (version 2) and, once extracted, the four LDS addresses they went to.
-template <int R, int NS, int FMT>
+// CB = 32-column blocks that are multiplied: 2, or 1 for a call of at most 32 columns that takes this
+// pass for the sake of sharing X between four bands (the X chunk keeps its 64-column shape; the
+// columns past N cost no memory traffic, and nothing of the second block is read, multiplied or stored).
+template <int R, int NS, int FMT, int CB>
 __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p) {
   constexpr int NB = kWideNB;
   constexpr uint32_t kRoundWords = FMT == 2 ? kRoundWords2 : 256u;  // words one round of 64 lanes stages
   static_assert(NS == 4 || NS == 8, "a body is 4 or 8 tiles");
+  static_assert(CB == 2 || NS == 8, "one column block: the wave's loads e < 4 are the first 32 columns only when a wave has a tile pair to itself");
+  constexpr int kXLoads = CB == 2 ? NS : 4;  // X loads of a chunk that this wave issues (the others would fetch columns past the call's)
   constexpr uint32_t kChunkBytes = NS * 4096u;
   extern __shared__ __align__(16) unsigned char lds[];
   const int lane = threadIdx.x & 63;
@@ -164,11 +170,11 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
 #pragma unroll
   for (int i = 0; i < kTileBytes / 1024; ++i) *(u32x4*)(tile + i * 1024 + lane * 16) = zero4;
 
-  float16v acc[kRowBlocks32][kColBlocks32];
+  float16v acc[kRowBlocks32][CB];
 #pragma unroll
   for (int rb = 0; rb < kRowBlocks32; ++rb)
 #pragma unroll
-    for (int cb = 0; cb < kColBlocks32; ++cb)
+    for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[rb][cb][r] = 0.f;
 
@@ -320,7 +326,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   // operations in order, so no wait separates re-zeroing, extraction and the fragment reads; the
   // MFMAs never wait for anything issued in their own step.  The last step of a body meets the other
   // waves before it reads B fragments from the chunk they filled together.
-  constexpr int kFragsA = kSteps16 * kRowBlocks32, kFragsB = kSteps16 * kColBlocks32;
+  constexpr int kFragsA = kSteps16 * kRowBlocks32, kFragsB = kSteps16 * CB;
   auto step = [&](auto it_, u32x4(&cur)[R], uint32_t& cn, uint32_t rel, u32x4(&nxt)[R], uint32_t nn, u32x4(&xs)[NS],
                   uint32_t kt_next, const half8(&fa)[kFragsA], const half8(&fb)[kFragsB], half8(&fan)[kFragsA],
                   half8(&fbn)[kFragsB]) {
@@ -328,16 +334,18 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
     constexpr int kZ = kUnscatter ? 4 * R : kTileBytes / 1024;  // re-zeroing operations
     constexpr int kE = 5 * R;                                   // extraction: per round a base select and four words
     constexpr int kOps = 1 + kZ + kE + 1 + kFragsA + kFragsB + 1;
-    constexpr int kMfmas = kSteps16 * kRowBlocks32 * kColBlocks32;
+    constexpr int kMfmas = kSteps16 * kRowBlocks32 * CB;
     uint32_t ebase = 0, eaddr = 0, ekeep = 0;
     auto other = [&](auto o_) {
       constexpr int o = decltype(o_)::value;
       if constexpr (o == 0) {
+        // (with one column block only the chunk's first four column groups hold columns of the call: the
+        // wave's loads e >= 4 would fetch nothing but zeros)
         if (FLS_ABLATE & 256) {
         } else if constexpr (it < NS / 2) {
-          xload2(xs, 2 * it, kt_next);
+          if constexpr (2 * it < kXLoads) xload2(xs, 2 * it, kt_next);
         } else {
-          xstore2(xs, 2 * (it - NS / 2));
+          if constexpr (2 * (it - NS / 2) < kXLoads) xstore2(xs, 2 * (it - NS / 2));
         }
       } else if constexpr (o < 1 + kZ) {
         constexpr int z = o - 1;
@@ -383,7 +391,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
       } else if constexpr (o < 2 + kZ + kE + kFragsA + kFragsB) {
         constexpr int j = o - 2 - kZ - kE - kFragsA;
         if (FLS_ABLATE & 256) fbn[j] = fb[j];
-        else fbn[j] = xfrag((it + 1) % NS, j % kColBlocks32, j / kColBlocks32, it == NS - 1);
+        else fbn[j] = xfrag((it + 1) % NS, j % CB, j / CB, it == NS - 1);
       } else {
         issue(cur, cn, it, rel);
       }
@@ -392,9 +400,9 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
     // accumulator lie eight apart
     static_for<0, kMfmas>([&](auto s_) {
       constexpr int s = decltype(s_)::value;
-      constexpr int ks = s / (kRowBlocks32 * kColBlocks32), rb = (s / kColBlocks32) % kRowBlocks32, cb = s % kColBlocks32;
-      if (FLS_ABLATE & 2) acc[rb][cb][0] += (float)fa[ks * kRowBlocks32 + rb][0] * (float)fb[ks * kColBlocks32 + cb][0];
-      else mfma_in_place(acc[rb][cb], fb[ks * kColBlocks32 + cb], fa[ks * kRowBlocks32 + rb]);
+      constexpr int ks = s / (kRowBlocks32 * CB), rb = (s / CB) % kRowBlocks32, cb = s % CB;
+      if (FLS_ABLATE & 2) acc[rb][cb][0] += (float)fa[ks * kRowBlocks32 + rb][0] * (float)fb[ks * CB + cb][0];
+      else mfma_in_place(acc[rb][cb], fb[ks * CB + cb], fa[ks * kRowBlocks32 + rb]);
       static_for<s * kOps / kMfmas, (s + 1) * kOps / kMfmas>(other);
     });
   };
@@ -420,7 +428,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
 #pragma unroll
     for (int j = 0; j < kFragsB; ++j)
       fb[j] = __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(
-                                            xrsrc, xd_lane + (j % kColBlocks32) * 4u * colgrp_bytes + kt * 64u + (j / kColBlocks32) * 32u, 0, 0));
+                                            xrsrc, xd_lane + (j % CB) * 4u * colgrp_bytes + kt * 64u + (j / CB) * 32u, 0, 0));
 #pragma unroll
     for (int j = 0; j < kFragsA; ++j) fa[j] = afrag(j % kRowBlocks32, j / kRowBlocks32);
 #pragma unroll
@@ -430,8 +438,8 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
 #pragma unroll
       for (int rb = 0; rb < kRowBlocks32; ++rb)
 #pragma unroll
-        for (int cb = 0; cb < kColBlocks32; ++cb)
-          acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[ks * kColBlocks32 + cb], fa[ks * kRowBlocks32 + rb], acc[rb][cb], 0, 0, 0);
+        for (int cb = 0; cb < CB; ++cb)
+          acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[ks * CB + cb], fa[ks * kRowBlocks32 + rb], acc[rb][cb], 0, 0, 0);
   };
 
   // The launcher picks R from the header the host remembers for this blob address.  If the memory
@@ -449,12 +457,12 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
     u32x4 xs[NS];
     uint32_t next_window = window_at(t0 + NS);
 #pragma unroll
-    for (int e = 0; e < NS; e += 2) xload2(xs, e, k0);
+    for (int e = 0; e < kXLoads; e += 2) xload2(xs, e, k0);
 #pragma unroll
     for (int i = 0; i < NS; ++i) issue(s[i], sn[i], i, (uint32_t)i);
     flip_chunks();  // the stores below fill the chunk the loop starts with
 #pragma unroll
-    for (int e = 0; e < NS; e += 2) xstore2(xs, e);
+    for (int e = 0; e < kXLoads; e += 2) xstore2(xs, e);
     flip_chunks();
     extract(s[0], sn[0]);
     chunk_barrier();
@@ -462,7 +470,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
 #pragma unroll
     for (int j = 0; j < kFragsA; ++j) fa0[j] = afrag(j % kRowBlocks32, j / kRowBlocks32);
 #pragma unroll
-    for (int j = 0; j < kFragsB; ++j) fb0[j] = xfrag(0, j % kColBlocks32, j / kColBlocks32, false);
+    for (int j = 0; j < kFragsB; ++j) fb0[j] = xfrag(0, j % CB, j / CB, false);
     uint32_t rel = NS;       // first tile the body's refills ask for
     uint32_t kt_next = k0;   // first K tile of the chunk the body loads
     for (uint32_t body = 0; body < bodies; ++body) {
@@ -491,13 +499,13 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   // The band's result for the slice: to C directly when the slice is all of K, else to the
   // partial-sum area [band][slice] that a second, small kernel adds up in slice order.
   if (p.S == 1) {
-    store_band32(p.C, p.M, p.N, n0, acc, band, lane);
+    store_band32<CB>(p.C, p.M, p.N, n0, acc, band, lane);
   } else {
     // [band][column group][slice][column block][row block][q][lane] float4: row (lane & 31) of the row block,
     // columns 8 q + 4 (lane >> 5) + (0..3) of the column block
     float4v* dst = (float4v*)p.parts + ((size_t)((band * p.G + cg) * p.S + slice) * (NB * kRowBlocks)) * 64 + lane;
 #pragma unroll
-    for (int cb = 0; cb < kColBlocks32; ++cb)
+    for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
       for (int rb = 0; rb < kRowBlocks32; ++rb)
 #pragma unroll
@@ -513,10 +521,11 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
 // pass, (column block of 32, row block of 32, q) in the 32x32 layout of the sparse pass (LAYOUT32).
 template <bool LAYOUT32>
 __global__ __launch_bounds__(256) void wide_reduce_kernel(WideParams p) {
+  const uint32_t per_band = LAYOUT32 ? p.cb * 16u : (uint32_t)(kWideNB * kRowBlocks);  // units of a band and column group that hold sums
   const uint32_t unit = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (unit >= p.bands * p.G * (kWideNB * kRowBlocks)) return;
+  if (unit >= p.bands * p.G * per_band) return;
   const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t bg = unit / (kWideNB * kRowBlocks), sub = unit - bg * (kWideNB * kRowBlocks);  // (band, column group), block
+  const uint32_t bg = unit / per_band, sub = unit - bg * per_band;  // (band, column group), block
   const uint32_t band = bg / p.G, n0 = p.n0 + (bg - band * p.G) * 64u;
   const float4v* src = (const float4v*)p.parts + ((size_t)bg * p.S * (kWideNB * kRowBlocks) + sub) * 64 + lane;
   float4v sum = {0.f, 0.f, 0.f, 0.f};
@@ -550,19 +559,20 @@ __global__ __launch_bounds__(256) void wide_reduce_kernel(WideParams p) {
   }
 }
 
-template <int R, int NS, int FMT>
+template <int R, int NS, int FMT, int CB = 2>
 static hipError_t launch_wide_variant(WideParams p, int cus, hipStream_t stream) {
   static std::atomic<bool> attr_done{false};  // per kernel variant; setting the attribute twice from two threads is harmless
   constexpr int kLds = wide_lds_bytes<NS>();
   if (!attr_done.load(std::memory_order_acquire)) {
-    hipError_t e = hipFuncSetAttribute((const void*)spmm_wide_kernel<R, NS, FMT>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
+    hipError_t e = hipFuncSetAttribute((const void*)spmm_wide_kernel<R, NS, FMT, CB>, hipFuncAttributeMaxDynamicSharedMemorySize, kLds);
     if (e != hipSuccess) return e;
     attr_done.store(true, std::memory_order_release);
   }
   const uint32_t quads = (p.bands + 3u) / 4u;
   p.S = wide_quad_slices(p.bands, p.G, p.KT, cus, NS);
   const uint32_t grid = (quads * p.S + 7u) / 8u * 8u * p.G;  // (group of bands, slice) pairs rounded up to eight, x column groups
-  hipLaunchKernelGGL((spmm_wide_kernel<R, NS, FMT>), dim3(grid), dim3(kWideWaves * 64), kLds, stream, p);
+  p.cb = CB;
+  hipLaunchKernelGGL((spmm_wide_kernel<R, NS, FMT, CB>), dim3(grid), dim3(kWideWaves * 64), kLds, stream, p);
   hipError_t e = hipGetLastError();
   if (e == hipSuccess && p.S > 1) e = launch_wide_reduce(p, true, stream);
   return e;
@@ -576,7 +586,7 @@ hipError_t launch_xpack(const _Float16* X, _Float16* xpack, uint32_t K, uint32_t
 }
 
 hipError_t launch_wide_reduce(const WideParams& p, bool layout32, hipStream_t stream) {
-  const uint32_t units = p.bands * p.G * (kWideNB * kRowBlocks);
+  const uint32_t units = p.bands * p.G * (layout32 ? p.cb * 16u : (uint32_t)(kWideNB * kRowBlocks));
   if (layout32) hipLaunchKernelGGL(wide_reduce_kernel<true>, dim3((units + 3) / 4), dim3(256), 0, stream, p);
   else hipLaunchKernelGGL(wide_reduce_kernel<false>, dim3((units + 3) / 4), dim3(256), 0, stream, p);
   return hipGetLastError();
@@ -602,6 +612,20 @@ hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, uint32_t groups, h
   p.S = 1;
   // rounds staged per tile (256 words in version 1, 64 groups = 192 words in version 2); the ring is 8 tiles
   // deep while the registers allow
+  // at most 32 columns in all: only the first 32-column block is multiplied (tiles of up to four rounds; the
+  // caller takes the narrow kernel for denser ones)
+  if (groups == 1 && a.N - n0 <= 32u) {
+    const uint32_t round = a.version == 2 ? kRoundWords2 : 256u;
+    if (a.version == 2) {
+      if (a.max_tile_words <= 2 * round) return launch_wide_variant<2, 8, 2, 1>(p, a.num_cus, stream);
+      if (a.max_tile_words <= 3 * round) return launch_wide_variant<3, 8, 2, 1>(p, a.num_cus, stream);
+      if (a.max_tile_words <= 4 * round) return launch_wide_variant<4, 8, 2, 1>(p, a.num_cus, stream);
+    } else {
+      if (a.max_tile_words <= 2 * round) return launch_wide_variant<2, 8, 1, 1>(p, a.num_cus, stream);
+      if (a.max_tile_words <= 3 * round) return launch_wide_variant<3, 8, 1, 1>(p, a.num_cus, stream);
+      if (a.max_tile_words <= 4 * round) return launch_wide_variant<4, 8, 1, 1>(p, a.num_cus, stream);
+    }
+  }
   if (a.version == 2) {
     const uint32_t round = kRoundWords2;
     if (a.max_tile_words <= 2 * round) return launch_wide_variant<2, 8, 2>(p, a.num_cus, stream);

@@ -97,7 +97,9 @@ def run_once(lib_path, blob, X, C, M, K, N, ws):
     return rc if rc != 0 else L.fls_check_workspace(stream)
 
 
-def time_variant(lib_path, blobs, X, C, M, K, N, ws, steps, warmup):
+def time_variant(lib_path, blobs, X, C, M, K, N, ws, steps, warmup, stats=None):
+    """Microseconds per call of fls_spmm through the build at lib_path; with `stats` (the blob's statistics, a ctypes
+    fls_stats) of fls_spmm_noalloc instead, the entry point that keeps to the narrow kernel for any shape."""
     import torch
 
     L = _bind(lib_path)
@@ -106,13 +108,32 @@ def time_variant(lib_path, blobs, X, C, M, K, N, ws, steps, warmup):
     assert L.fls_set_workspace(vp(ws.data_ptr()), ws.numel(), stream) == 0
     calls = [vp(b.data_ptr()) for b in blobs]
     x, c = vp(X.data_ptr()), vp(C.data_ptr())
+    if stats is not None:
+        L.fls_spmm_noalloc.argtypes = [vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, vp]
+        st = ctypes.byref(stats)
+
+        def one(i):
+            return L.fls_spmm_noalloc(calls[i % len(calls)], st, x, c, M, K, N, stream)
+    else:
+        def one(i):
+            return L.fls_spmm(calls[i % len(calls)], x, c, M, K, N, stream)
+    # untimed launches for 50 ms first: after an idle period (input generation, the build before) the chip's
+    # clocks take some hundred launches to come up, which the first variant timed would otherwise pay for
+    import time
+    t_end = time.perf_counter() + 0.05
+    i = 0
+    while time.perf_counter() < t_end:
+        for _ in range(32):
+            assert one(i) == 0
+            i += 1
+        torch.cuda.synchronize()
     for i in range(warmup):
-        assert L.fls_spmm(calls[i % len(calls)], x, c, M, K, N, stream) == 0
+        assert one(i) == 0
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for i in range(steps):
-        L.fls_spmm(calls[i % len(calls)], x, c, M, K, N, stream)
+        one(i)
     e1.record()
     torch.cuda.synchronize()
     return e0.elapsed_time(e1) / steps * 1e3
@@ -126,6 +147,9 @@ def main():
     ap.add_argument("--keep", default="", help="folder for the builds (kept); default: a temporary directory")
     ap.add_argument("--build-only", action="store_true")
     ap.add_argument("--prebuilt", default="", help="folder with builds made by --build-only")
+    ap.add_argument("--entry", choices=("spmm", "noalloc"), default="spmm",
+                    help="noalloc: time fls_spmm_noalloc (N <= 32), which keeps to the narrow kernel on shapes where "
+                         "fls_spmm takes the 64-column pass for 17 - 32 columns")
     args = ap.parse_args()
 
     tmp = None
@@ -161,9 +185,12 @@ def main():
     C = torch.empty((N, M), dtype=torch.float16, device="cuda")
     ws = torch.empty(fls.fls_workspace_bytes(M, K, N), dtype=torch.uint8, device="cuda")
     alg = st["bytes_total"] + 2 * K * N + 2 * M * N
+    stats = None
+    if args.entry == "noalloc":
+        stats = fls.FlsStats(**{k: st[k] for k, _ in fls.FlsStats._fields_})
     for name, mask in VARIANTS:
-        us = time_variant(libs[mask], blobs, X, C, M, K, N, ws, args.steps, args.warmup)
-        print(json.dumps({"config": args.config, "variant": name, "FLS_ABLATE": mask, "us": round(us, 2),
+        us = time_variant(libs[mask], blobs, X, C, M, K, N, ws, args.steps, args.warmup, stats)
+        print(json.dumps({"config": args.config, "variant": name, "FLS_ABLATE": mask, "entry": args.entry, "us": round(us, 2),
                           "GBps_on_algorithmic_bytes": round(alg / us / 1e3, 1)}), flush=True)
     if tmp:
         tmp.cleanup()

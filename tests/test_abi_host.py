@@ -34,7 +34,8 @@ def test_sizes_and_bounds(fls):
     assert fls.fls_compress_bound(1024, 1024) == 64 + 4 * 272 + 4 * 1024 * 1024
     # 4 MiB control area + [512 workgroups][column blocks][128 x 16] fp32
     assert fls.fls_workspace_bytes(1024, 1024, 8) == (4 << 20) + 512 * 1 * 2048 * 4
-    assert fls.fls_workspace_bytes(1024, 1024, 17) == (4 << 20) + 512 * 2 * 2048 * 4
+    # from 17 columns on: the 64-column pass's [4 x 512 bands x slices][4 column blocks][128 x 16] fp32
+    assert fls.fls_workspace_bytes(1024, 1024, 17) == (4 << 20) + 4 * 512 * 4 * 2048 * 4
     assert fls.fls_workspace_bytes(1024, 1024, 256) == (4 << 20) + 4 * 512 * 4 * 2048 * 4 + 1024 * 256 * 2
     assert fls.fls_workspace_bytes(1000, 1024, 8) == 0 and fls.fls_workspace_bytes(1024, 1024, 8193) == 0
     assert fls.TILE_M == 128 and fls.TILE_K == 32

@@ -68,10 +68,11 @@ def _dense(fls, Wbits, Xbits):
     return C.cpu().numpy()
 
 
-@pytest.mark.parametrize("name", ["C2", "C3", "C4"])
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "S1"])
 def test_named_configuration_whole_c_and_blob(fls, oracle_mod, name):
     """C2 (N = 16, one band per workgroup), C3 (N = 32, two column blocks per wave), C4 (N = 64: the 64-column
-    pass): blob byte-exact against the oracle's compressor, every element of C against the oracle."""
+    pass), S1 (C4's matrix at N = 32: the 64-column pass with one 32-column block multiplied): blob byte-exact
+    against the oracle's compressor, every element of C against the oracle."""
     cfg = wl.CONFIGS[name]
     W, X = wl.make_inputs(cfg)
     blob, st, C = _spmm(fls, W, X)
@@ -89,10 +90,11 @@ def sweep_w32():
 
 
 # one point per kernel path of the sweep: 96 bands cut between all workgroups with the hand-over through
-# memory (N = 8, N = 32), the 64-column pass with K slices (N = 64), two such passes (N = 128), and the
-# row-skewed mask at 50 %, whose densest tiles need the ten-round register ring of the 64-column pass
+# memory (N = 8, N = 32 at 60 %), the 64-column pass with K slices (N = 64), two such passes (N = 128), the
+# row-skewed mask at 50 %, whose densest tiles need the ten-round register ring of the 64-column pass, and
+# 32 columns at 90 %, which take the 64-column pass with one column block
 SWEEP_POINTS = [("uniform", 0.8, 8), ("uniform", 0.6, 32), ("uniform", 0.9, 64), ("uniform", 0.7, 128),
-                ("row_skewed", 0.5, 64), ("row_skewed", 0.5, 16), ("uniform", 0.9, 256)]
+                ("row_skewed", 0.5, 64), ("row_skewed", 0.5, 16), ("uniform", 0.9, 256), ("uniform", 0.9, 32)]
 
 
 @pytest.mark.parametrize("mask,beta,N", SWEEP_POINTS, ids=[f"{m}-{int(b * 100)}-N{n}" for m, b, n in SWEEP_POINTS])

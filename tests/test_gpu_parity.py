@@ -152,6 +152,33 @@ def test_spmm_wide_n(fls, oracle_mod, N):
     assert _rel_err(C, oracle_mod.ref_spmm_f64(W, X)) <= TOL
 
 
+@pytest.mark.parametrize("fmt", [1, 2])
+@pytest.mark.parametrize("M,K,beta,N", [(512, 12288, 0.9, 32), (640, 16384, 0.8, 17), (640, 12288, 0.85, 24),
+                                        (512, 12288, 0.8, 96), (384, 12288, 0.6, 32), (640, 32768, 0.9, 32),
+                                        (256, 40960, 0.8, 20)])
+def test_17_to_32_columns_on_long_bands(fls, oracle_mod, M, K, beta, N, fmt):
+    """Calls (or the rest of a call) of 17 - 32 columns on bands of at least 384 K tiles (1024 in format version 2:
+    the last two shapes) take the 64-column pass with only its first 32-column block multiplied (sparse tiles:
+    90 / 85 / 80 %), the narrow kernel otherwise (60 %).  Five bands: the second workgroup of a K slice has three waves without a band.  N = 96: a group of 64
+    columns, then the rest of 32.  Whole C against the oracle, both format versions."""
+    import torch
+
+    W = wl.prune_uniform(wl.gen_weights_f32(M, K, 1300 + N), beta, 1301 + N)
+    Xb = wl.gen_x(N, K, 1302 + N)
+    blob, st = (fls.fls_compress_v2 if fmt == 2 else fls.fls_compress)(_dev_w(W))
+    X = torch.from_numpy(Xb.view(np.float16)).cuda()
+    C = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+    fls.ensure_workspace(M, K, N)
+    fls.fls_spmm(blob, X, C, M, K, N)
+    fls.fls_spmm(blob, X, C, M, K, N)  # the second call finds the header remembered
+    torch.cuda.synchronize()
+    fls.fls_check_workspace()
+    fls.fls_forget(blob)
+    out = C.cpu().numpy()
+    assert np.isfinite(out).all()
+    assert _rel_err(out, oracle_mod.ref_spmm_f64(W, Xb)) <= TOL
+
+
 @pytest.mark.parametrize("N", [384, 512, 1000, 4096])
 def test_spmm_and_dense_non_skinny_n(fls, oracle_mod, N):
     """N beyond the skinny range (Sec. 6.2, non-skinny shapes): passes of 64 columns, a ragged last one for
