@@ -337,7 +337,7 @@ def measure_config(name, args, with_dense, with_cpu):
     t_mfma_us = flops / (MFMA_F16_PEAK_TFLOPS * 1e6)
     # which kernels the call runs (a label; the library decides): the 64-column pass for more than 32 columns, and for
     # 17 - 32 columns on sparse tiles and long bands (the rule of wide32_pays in csrc/fls_launch.h)
-    pass32 = 16 < N <= 32 and st["max_tile_words"] <= 1024 and K // 32 >= 384 and args.entry != "noalloc"
+    pass32 = 16 < N <= 32 and st["max_tile_words"] <= 2560 and K // 32 >= 384 and args.entry != "noalloc"
     narrow = (N <= 32 and not pass32) or st["max_tile_words"] > 2560
     kernels = "fls::spmm_kernel" if narrow else "fls::spmm_wide_kernel + fls::wide_reduce_kernel"
     traffic = MEASURED_TRAFFIC.get(name)

@@ -81,16 +81,20 @@ inline size_t parts_floats(uint32_t N) {
 }
 
 // A call (or the rest of a call) of 17 - 32 columns: the narrow kernel with two column blocks per wave, or the
-// 64-column pass multiplying only its first 32-column block.  Every tile asks for 2 KB of X here, more than a
+// 64-column pass multiplying only its first 32-column block.  Every tile asks for 2 KB of X here, as much as a
 // sparse tile's words, and the narrow kernel's waves fetch X from L2 each for themselves; the pass shares X between
-// four bands through LDS.  Measured (us, narrow / pass): 12288 x 49152 at 90 % 73.7 / 63.2, at 80 % 105.0 / 93.7;
-// 49152 x 12288 74.3 / 70.0 and 104.6 / 101.7; 12288 x 12288 28.2 / 27.3 and 37.0 / 35.3; but 28672 x 7168
-// 28.7 / 31.4 and 40.3 / 41.6, 7168 x 7168 16.0 / 19.0: the pass pays its second kernel and needs long bands.
-// So: tiles of up to four rounds (the variants built for one column block) and at least 384 K tiles per band.
+// four bands through LDS.  Measured in format version 1 (us, narrow / pass): 12288 x 49152 at 90 % 73.7 / 63.2, 80 %
+// 105.0 / 93.7, 70 % 135.5 / 117.5, 60 % 164.4 / 150.0, 50 % 200.1 / 184.7; 49152 x 12288 at 90 - 60 % 74.3 / 70.0,
+// 104.6 / 101.7, 134.7 / 128.6, 164.4 / 157.6; 12288 x 24576 at 70 % 73.1 / 66.5; 12288 x 12288 at 90 - 50 % 28.2 / 27.3,
+// 37.0 / 35.3, 44.2 / 41.3, 51.7 / 49.6, 60.8 / 58.5; but 28672 x 7168 at 90 % 28.7 / 31.4, at 80 % 40.3 / 41.6,
+// 7168 x 7168 16.0 / 19.0: the pass pays its second kernel and needs long bands.  So, in version 1: bands of at
+// least 384 K tiles, any tile the pass can stage (ten rounds).
 // In format version 2 the narrow kernel has a quarter fewer bytes to wait for and stays ahead longer (12288 x
-// 12288: 32.9 / 34.7 at 80 %, 26.2 / 27.2 at 90 %; 12288 x 49152 at 90 %: 65.6 / 62.7): from 1024 K tiles on.
+// 12288: 32.9 / 34.7 at 80 %, 26.2 / 27.2 at 90 %; 12288 x 49152 at 90 %: 65.6 / 62.7, at 70 %: 114.1 / 116.1; 49152 x
+// 12288 at 70 %: 113.8 / 136.6): tiles of up to four rounds on bands of at least 1024 K tiles.
 inline bool wide32_pays(uint32_t max_tile_words, uint32_t round_words, uint32_t KT, uint32_t version) {
-  return max_tile_words <= 4u * round_words && KT >= (version == 2u ? 1024u : 384u);
+  if (version == 2u) return max_tile_words <= 4u * round_words && KT >= 1024u;
+  return max_tile_words <= 10u * round_words && KT >= 384u;
 }
 
 // Workspace bytes for X repacked into MFMA fragment order, [K tile][column block][lane][8 halves]

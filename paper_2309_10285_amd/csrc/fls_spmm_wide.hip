@@ -136,8 +136,10 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
   constexpr int NB = kWideNB;
   constexpr uint32_t kRoundWords = FMT == 2 ? kRoundWords2 : 256u;  // words one round of 64 lanes stages
   static_assert(NS == 4 || NS == 8, "a body is 4 or 8 tiles");
-  static_assert(CB == 2 || NS == 8, "one column block: the wave's loads e < 4 are the first 32 columns only when a wave has a tile pair to itself");
-  constexpr int kXLoads = CB == 2 ? NS : 4;  // X loads of a chunk that this wave issues (the others would fetch columns past the call's)
+  // X loads of a chunk that this wave issues.  With one column block and eight-tile bodies a wave has a tile pair to
+  // itself and its loads e >= 4 are columns 32 - 63: never issued.  (With four-tile bodies two waves share a pair and
+  // the odd one's loads are those columns; they are issued and leave the buffer: zeros, no memory traffic.)
+  constexpr int kXLoads = CB == 1 && NS == 8 ? 4 : NS;
   constexpr uint32_t kChunkBytes = NS * 4096u;
   extern __shared__ __align__(16) unsigned char lds[];
   const int lane = threadIdx.x & 63;
@@ -612,8 +614,7 @@ hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, uint32_t groups, h
   p.S = 1;
   // rounds staged per tile (256 words in version 1, 64 groups = 192 words in version 2); the ring is 8 tiles
   // deep while the registers allow
-  // at most 32 columns in all: only the first 32-column block is multiplied (tiles of up to four rounds; the
-  // caller takes the narrow kernel for denser ones)
+  // at most 32 columns in all: only the first 32-column block is multiplied (the variants that wide32_pays can ask for)
   if (groups == 1 && a.N - n0 <= 32u) {
     const uint32_t round = a.version == 2 ? kRoundWords2 : 256u;
     if (a.version == 2) {
@@ -624,6 +625,9 @@ hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, uint32_t groups, h
       if (a.max_tile_words <= 2 * round) return launch_wide_variant<2, 8, 1, 1>(p, a.num_cus, stream);
       if (a.max_tile_words <= 3 * round) return launch_wide_variant<3, 8, 1, 1>(p, a.num_cus, stream);
       if (a.max_tile_words <= 4 * round) return launch_wide_variant<4, 8, 1, 1>(p, a.num_cus, stream);
+      if (a.max_tile_words <= 6 * round) return launch_wide_variant<6, 4, 1, 1>(p, a.num_cus, stream);
+      if (a.max_tile_words <= 8 * round) return launch_wide_variant<8, 4, 1, 1>(p, a.num_cus, stream);
+      if (a.max_tile_words <= 10 * round) return launch_wide_variant<10, 4, 1, 1>(p, a.num_cus, stream);
     }
   }
   if (a.version == 2) {

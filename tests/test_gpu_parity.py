@@ -155,12 +155,14 @@ def test_spmm_wide_n(fls, oracle_mod, N):
 @pytest.mark.parametrize("fmt", [1, 2])
 @pytest.mark.parametrize("M,K,beta,N", [(512, 12288, 0.9, 32), (640, 16384, 0.8, 17), (640, 12288, 0.85, 24),
                                         (512, 12288, 0.8, 96), (384, 12288, 0.6, 32), (640, 32768, 0.9, 32),
-                                        (256, 40960, 0.8, 20)])
+                                        (256, 40960, 0.8, 20), (256, 12288, 0.45, 32), (384, 6144, 0.8, 32)])
 def test_17_to_32_columns_on_long_bands(fls, oracle_mod, M, K, beta, N, fmt):
-    """Calls (or the rest of a call) of 17 - 32 columns on bands of at least 384 K tiles (1024 in format version 2:
-    the last two shapes) take the 64-column pass with only its first 32-column block multiplied (sparse tiles:
-    90 / 85 / 80 %), the narrow kernel otherwise (60 %).  Five bands: the second workgroup of a K slice has three waves without a band.  N = 96: a group of 64
-    columns, then the rest of 32.  Whole C against the oracle, both format versions."""
+    """Calls (or the rest of a call) of 17 - 32 columns on bands of at least 384 K tiles take the 64-column pass
+    with only its first 32-column block multiplied, whatever the density of the tiles (90 ... 45 %: the rings of two
+    to ten rounds) - in format version 2 only sparse tiles on bands of at least 1024 K tiles (the shapes with
+    K = 32768 and 40960) - and the narrow kernel otherwise (K = 6144).  Five bands: the second workgroup of a K slice
+    has three waves without a band.  N = 96: a group of 64 columns, then the rest of 32.  Whole C against the oracle.
+    """
     import torch
 
     W = wl.prune_uniform(wl.gen_weights_f32(M, K, 1300 + N), beta, 1301 + N)
