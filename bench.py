@@ -291,6 +291,22 @@ def run_layer(args):
 MFMA_F16_PEAK_TFLOPS = 2500.0  # MI355X published dense fp16 matrix rate
 
 
+def _pass32_rule(max_tile_words, KT, bands, cus=256):
+    """The library's rule (wide32_pays in csrc/fls_launch.h, format version 1) for giving a call of 17 - 32 columns to
+    the 64-column pass, restated for the kernel label of the bench line only."""
+    if max_tile_words > 2560:
+        return False
+    if KT >= 384:
+        return True
+    if KT < 288 or max_tile_words <= 512:
+        return False
+    body = 8 if max_tile_words <= 1024 else 4
+    units = (bands + 3) // 4
+    S = max(1, min(cus // units if units < cus else 1, max(1, KT // (2 * body))))
+    bodies = KT // body
+    return -(-bodies // S) * S * 10 <= bodies * 11
+
+
 def measure_config(name, args, with_dense, with_cpu):
     """Times fls_spmm on one named configuration (inputs resident in HBM, weights rotated over more than 1 GB of
     copies), the streaming-read ceiling over the same blobs, optionally the dense pair; checks the whole of C
@@ -337,7 +353,7 @@ def measure_config(name, args, with_dense, with_cpu):
     t_mfma_us = flops / (MFMA_F16_PEAK_TFLOPS * 1e6)
     # which kernels the call runs (a label; the library decides): the 64-column pass for more than 32 columns, and for
     # 17 - 32 columns on sparse tiles and long bands (the rule of wide32_pays in csrc/fls_launch.h)
-    pass32 = 16 < N <= 32 and st["max_tile_words"] <= 2560 and K // 32 >= 384 and args.entry != "noalloc"
+    pass32 = 16 < N <= 32 and args.entry != "noalloc" and _pass32_rule(st["max_tile_words"], K // 32, M // 128)
     narrow = (N <= 32 and not pass32) or st["max_tile_words"] > 2560
     kernels = "fls::spmm_kernel" if narrow else "fls::spmm_wide_kernel + fls::wide_reduce_kernel"
     traffic = MEASURED_TRAFFIC.get(name)

@@ -92,9 +92,19 @@ inline size_t parts_floats(uint32_t N) {
 // In format version 2 the narrow kernel has a quarter fewer bytes to wait for and stays ahead longer (12288 x
 // 12288: 32.9 / 34.7 at 80 %, 26.2 / 27.2 at 90 %; 12288 x 49152 at 90 %: 65.6 / 62.7, at 70 %: 114.1 / 116.1; 49152 x
 // 12288 at 70 %: 113.8 / 136.6): tiles of up to four rounds on bands of at least 1024 K tiles.
-inline bool wide32_pays(uint32_t max_tile_words, uint32_t round_words, uint32_t KT, uint32_t version) {
+// Bands of 288 - 383 K tiles: the pass still wins where its K slices come out even and the tiles are not the
+// sparsest (27648 x 9216 at 70 % 61.9 / 59.0, at 80 % 49.0 / 47.2, at 90 % 34.8 / 35.1; 20480 x 9216 at 80 % 42.1 /
+// 37.7; 12288 x 10240 at 80 % 32.6 / 31.2, at 60 % 45.3 / 43.8; but 12288 x 9216 at 80 %, whose ten slices are
+// three or four bodies long, 30.5 / 31.0, and 12288 x 8192 at 80 % 27.5 / 30.6).
+inline bool wide32_pays(uint32_t max_tile_words, uint32_t round_words, uint32_t KT, uint32_t version, uint32_t bands, int cus) {
   if (version == 2u) return max_tile_words <= 4u * round_words && KT >= 1024u;
-  return max_tile_words <= 10u * round_words && KT >= 384u;
+  if (max_tile_words > 10u * round_words) return false;
+  if (KT >= 384u) return true;
+  if (KT < 288u || max_tile_words <= 2u * round_words) return false;
+  // the longest K slice at most a tenth above the mean (bodies of 8 tiles up to four rounds, of 4 beyond: as the pass picks them)
+  const uint32_t body = max_tile_words <= 4u * round_words ? 8u : 4u;
+  const uint32_t bodies = KT / body, S = wide_quad_slices(bands, 1u, KT, cus, body);
+  return (uint64_t)((bodies + S - 1u) / S) * S * 10u <= (uint64_t)bodies * 11u;
 }
 
 // Workspace bytes for X repacked into MFMA fragment order, [K tile][column block][lane][8 halves]

@@ -451,7 +451,7 @@ hipError_t launch_spmm(const SpmmLaunch& a, hipStream_t stream) {
       p.X = a.X;
       e = v2 ? launch_r<1, 8, 2>(R, p, grid, stream) : launch_r<1, 8, 1>(R, p, grid, stream);
       n0 += 16;
-    } else if (left <= 32 && a.wide32 && wide32_pays(a.max_tile_words, round_words, a.K / kTileK, a.version)) {
+    } else if (left <= 32 && a.wide32 && wide32_pays(a.max_tile_words, round_words, a.K / kTileK, a.version, a.M / kTileM, a.num_cus)) {
       e = launch_spmm_wide(a, n0, 1, stream);  // multiplies its first 32-column block only
       n0 += 32;
     } else if (left <= 32 || !wide_ok) {

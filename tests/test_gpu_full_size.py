@@ -70,9 +70,9 @@ def _dense(fls, Wbits, Xbits):
 
 @pytest.mark.parametrize("name", ["C2", "C3", "C4", "S1"])
 def test_named_configuration_whole_c_and_blob(fls, oracle_mod, name):
-    """C2 (N = 16, one band per workgroup), C3 (N = 32, two column blocks per wave), C4 (N = 64: the 64-column
-    pass), S1 (C4's matrix at N = 32: the 64-column pass with one 32-column block multiplied): blob byte-exact
-    against the oracle's compressor, every element of C against the oracle."""
+    """C2 (N = 16, one band per workgroup), C4 (N = 64: the 64-column pass), C3 and S1 (N = 32 on long bands: the
+    64-column pass with one 32-column block multiplied): blob byte-exact against the oracle's compressor, every
+    element of C against the oracle."""
     cfg = wl.CONFIGS[name]
     W, X = wl.make_inputs(cfg)
     blob, st, C = _spmm(fls, W, X)
@@ -82,6 +82,23 @@ def test_named_configuration_whole_c_and_blob(fls, oracle_mod, name):
     del ref_blob, blob
     err, band = _whole_c_err(C, oracle_mod.ref_spmm_f64(W, X))
     assert err <= TOL, (name, "worst band", band)
+
+
+def test_c3_in_the_narrow_kernel_whole_c(fls, oracle_mod):
+    """C3 through fls_spmm_noalloc, which keeps to the narrow kernel (two column blocks per wave, one band per
+    workgroup) where fls_spmm takes the 64-column pass: every element of C against the oracle."""
+    import torch
+
+    cfg = wl.CONFIGS["C3"]
+    W, X = wl.make_inputs(cfg)
+    blob, st = fls.fls_compress(torch.from_numpy(W.view(np.float16)).cuda())
+    Xd = torch.from_numpy(X.view(np.float16)).cuda()
+    C = torch.full((cfg.N, cfg.M), float("nan"), dtype=torch.float16, device="cuda")
+    fls.fls_spmm_noalloc(blob, st, Xd, C, cfg.M, cfg.K, cfg.N)
+    torch.cuda.synchronize()
+    fls.fls_check_workspace()
+    err, band = _whole_c_err(C.cpu().numpy(), oracle_mod.ref_spmm_f64(W, X))
+    assert err <= TOL, ("worst band", band)
 
 
 @pytest.fixture(scope="module")
