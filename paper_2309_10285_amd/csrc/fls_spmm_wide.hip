@@ -518,7 +518,7 @@ __global__ __launch_bounds__(kWideWaves * 64) void spmm_wide_kernel(WideParams p
 }
 
 // Adds the S partial results of every band in slice order, converts, writes C.  One wave per 1 KB
-// unit of a band's partial result (32 units): S loads of 16 B per lane, all issued before the first is
+// unit of a band's partial result (32 units; 16 when the pass multiplied one column block): S loads of 16 B per lane, all issued before the first is
 // used.  A unit is (column block of 16, row block of 16) in the 16x16 accumulator layout of the dense
 // pass, (column block of 32, row block of 32, q) in the 32x32 layout of the sparse pass (LAYOUT32).
 template <bool LAYOUT32>
@@ -612,9 +612,11 @@ hipError_t launch_spmm_wide(const SpmmLaunch& a, uint32_t n0, uint32_t groups, h
   p.KT = a.K / kTileK;
   p.bands = a.M / kTileM;
   p.S = 1;
-  // rounds staged per tile (256 words in version 1, 64 groups = 192 words in version 2); the ring is 8 tiles
-  // deep while the registers allow
-  // at most 32 columns in all: only the first 32-column block is multiplied (the variants that wide32_pays can ask for)
+  // Variants by rounds staged per tile (256 words in version 1, 64 groups = 192 words in version 2); the ring is
+  // 8 tiles deep while the registers allow.
+  // At most 32 columns in all: only the first 32-column block is multiplied (the variants that wide32_pays can
+  // ask for; anything else - a header that is out of date - falls through to the two-block variants, which are right
+  // for any N).
   if (groups == 1 && a.N - n0 <= 32u) {
     const uint32_t round = a.version == 2 ? kRoundWords2 : 256u;
     if (a.version == 2) {
