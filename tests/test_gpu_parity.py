@@ -144,7 +144,7 @@ def test_spmm_matches_oracle(fls, oracle_mod, name, W, N):
 
 @pytest.mark.parametrize("N", [33, 48, 80, 96, 100, 128, 256])
 def test_spmm_wide_n(fls, oracle_mod, N):
-    # column groups: 64-column passes (X repacked into fragment order) followed by a 16- or 32-column rest
+    # column groups of 64 in one launch, the last one partly empty (33, 48: a single group; 80, 96, 100: two)
     W = CASES[3][1]
     M, K = W.shape
     X = wl.gen_x(N, K, 5)
@@ -161,7 +161,7 @@ def test_17_to_32_columns_on_long_bands(fls, oracle_mod, M, K, beta, N, fmt):
     with only its first 32-column block multiplied, whatever the density of the tiles (90 ... 45 %: the rings of two
     to ten rounds) - in format version 2 only sparse tiles on bands of at least 1024 K tiles (the shapes with
     K = 32768 and 40960) - and the narrow kernel otherwise (K = 6144).  Five bands: the second workgroup of a K slice
-    has three waves without a band.  N = 96: a group of 64 columns, then the rest of 32.  Whole C against the oracle.
+    has three waves without a band.  N = 96: two groups of 64 columns in one launch, the second half empty.  Whole C against the oracle.
     """
     import torch
 
@@ -183,8 +183,8 @@ def test_17_to_32_columns_on_long_bands(fls, oracle_mod, M, K, beta, N, fmt):
 
 @pytest.mark.parametrize("N", [384, 512, 1000, 4096])
 def test_spmm_and_dense_non_skinny_n(fls, oracle_mod, N):
-    """N beyond the skinny range (Sec. 6.2, non-skinny shapes): passes of 64 columns, a ragged last one for
-    N = 1000 (40 columns: a 32-column and a 16-column pass); byte offsets into X and C reach tens of MB."""
+    """N beyond the skinny range (Sec. 6.2, non-skinny shapes): groups of 64 columns in one launch, a ragged last
+    one for N = 1000 (40 of its 64 columns exist); byte offsets into X and C reach tens of MB."""
     W = CASES[4][1]  # 1536 x 2048, 90 % magnitude-pruned: bands cut between workgroups, K slices
     M, K = W.shape
     X = wl.gen_x(N, K, 700 + N)
@@ -471,26 +471,32 @@ def test_piece_boundary_at_the_edge_of_the_offset_window(fls, oracle_mod):
 
 
 def test_split_bands_after_wide_passes_many_repeats(fls, oracle_mod):
-    """N = 222 on a matrix whose bands are cut between workgroups: three 64-column passes, then a 32-column pass
-    whose partial-sum slots lie where the wide passes' partial results were a moment ago.  A hand-over that raised
-    its flag before its partial sum had left the XCD's L2 gave a wrong band about once in a thousand such calls;
-    the first result is checked against the oracle in full, then 3000 more calls must repeat it to within
-    fp16 rounding (inside a workgroup the waves' sums are added in the order they finish, so the last bit may
-    differ; a wrong band is off by tens of percent)."""
+    """222 columns on a matrix whose bands are cut between workgroups, as two calls on one workspace: 192 columns
+    through the 64-column pass (three groups in one launch), then 30 columns through the narrow kernel, whose
+    partial-sum slots lie where the pass's partial results were a moment ago.  A hand-over that raised its flag
+    before its partial sum had left the XCD's L2 gave a wrong band about once in a thousand such sequences; the
+    first result is checked against the oracle in full, then 3000 more rounds must repeat it to within fp16
+    rounding (inside a workgroup the waves' sums are added in the order they finish, so the last bit may differ; a
+    wrong band is off by tens of percent)."""
     import torch
 
-    M, K, N = 24960, 9216, 222
+    M, K, N, NW = 24960, 9216, 222, 192
     W = wl.prune_uniform(wl.gen_weights_f32(M, K, 91), 0.9, 92)
     X = wl.gen_x(N, K, 93)
     blob, st = fls.fls_compress(_dev_w(W))
     Xd = torch.from_numpy(X.view(np.float16)).cuda()
     fls.ensure_workspace(M, K, N)
+
+    def both(C):
+        fls.fls_spmm(blob, Xd[:NW], C[:NW], M, K, NW)
+        fls.fls_spmm(blob, Xd[NW:], C[NW:], M, K, N - NW)
+
     first = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
-    fls.fls_spmm(blob, Xd, first, M, K, N)
+    both(first)
     torch.cuda.synchronize()
     got = first.cpu().numpy()
     assert not np.isnan(got).any()
-    ref = oracle_mod.ref_spmm_f64(W, X)  # the whole of C: every later call is compared with this first result
+    ref = oracle_mod.ref_spmm_f64(W, X)  # the whole of C: every later round is compared with this first result
     assert float(np.abs(got.astype(np.float64) - ref).max()) / float(np.abs(ref).max()) <= TOL
     del ref
     C = torch.empty_like(first)
@@ -499,7 +505,7 @@ def test_split_bands_after_wide_passes_many_repeats(fls, oracle_mod):
     worst = torch.zeros((), device="cuda")
     for rep in range(3000):
         C.fill_(float("nan"))
-        fls.fls_spmm(blob, Xd, C, M, K, N)
+        both(C)
         worst = torch.maximum(worst, torch.nan_to_num((C.float() - ref32).abs(), nan=float("inf")).max())
     assert float(worst) / scale <= TOL
     fls.fls_check_workspace()
