@@ -344,15 +344,14 @@ def test_very_long_k(fls, oracle_mod):
     assert _rel_err(_run_dense(fls, W, X[:16], 16), oracle_mod.ref_spmm_f64(W, X[:16])) <= TOL
 
 
-@pytest.mark.parametrize("N", [16, 64, 100])
-def test_blob_replaced_in_place_behind_the_librarys_back(fls, oracle_mod, N):
+@pytest.mark.parametrize("M,K,N", [(1024, 2048, 16), (1024, 2048, 64), (1024, 2048, 100), (256, 12288, 32)])
+def test_blob_replaced_in_place_behind_the_librarys_back(fls, oracle_mod, M, K, N):
     """A sparse blob is used at an address, then the bytes of a denser blob of the same shape are copied over it
     without fls_forget: the kernel variant is still picked for the sparse one (a ring too short for the new tiles),
-    and the results must be right all the same, in the 32-column passes and in the 64-column pass.  Then the other
-    way round (a ring longer than needed)."""
+    and the results must be right all the same, in the 32-column passes, in the 64-column pass and (32 columns on
+    bands of 384 K tiles) in that pass with one column block.  Then the other way round (a ring longer than needed)."""
     import torch
 
-    M, K = 1024, 2048
     W32 = wl.gen_weights_f32(M, K, 41)
     sparse, dense = wl.prune_uniform(W32, 0.9, 42), wl.prune_uniform(W32, 0.45, 43)
     X = wl.gen_x(N, K, 44)
